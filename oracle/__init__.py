@@ -1,0 +1,118 @@
+"""ctypes front end of the CPU oracle (``pipad_oracle.cpp``).  TEST INFRASTRUCTURE ONLY.
+
+Only the tests, the smoke check and the benchmark's CPU-baseline leg may import this package; the
+HIP library never does, and this package never imports the HIP library.  Inputs are edge lists
+(directed ``(row, col)`` pairs, host numpy arrays); see the C++ file for what each call computes and
+which passages of the paper it follows (Eq. 1 with the symmetric GCN normalisation; the overlap /
+exclusive regrouping of Sections 4.1-4.2).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pipad_oracle.cpp")
+_LIB = os.path.join(_HERE, "libpipad_oracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with g++ (always when force, else only if the library is absent)."""
+    if force or not os.path.exists(_LIB):
+        cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread", "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        lib = ctypes.CDLL(_LIB)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        lib.pipad_oracle_overlap_create.restype = vp
+        lib.pipad_oracle_overlap_create.argtypes = [i32, i32, vp, vp, vp]
+        lib.pipad_oracle_overlap_destroy.restype = None
+        lib.pipad_oracle_overlap_destroy.argtypes = [vp]
+        lib.pipad_oracle_overlap_nnz.restype = i64
+        lib.pipad_oracle_overlap_nnz.argtypes = [vp, i32]
+        lib.pipad_oracle_overlap_csr.restype = ctypes.c_int
+        lib.pipad_oracle_overlap_csr.argtypes = [vp, i32, vp, vp]
+        lib.pipad_oracle_aggregate.restype = ctypes.c_int
+        lib.pipad_oracle_aggregate.argtypes = [i32, i64, vp, vp, i32, vp, i64, vp, i64, vp, vp, i32]
+        lib.pipad_oracle_hardware_threads.restype = ctypes.c_int
+        lib.pipad_oracle_hardware_threads.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def hardware_threads() -> int:
+    return int(_load().pipad_oracle_hardware_threads())
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+Csr = Tuple[np.ndarray, np.ndarray]  # (rowptr int32[n+1], col int32[nnz])
+
+
+def overlap(n: int, edge_lists: Sequence[Tuple[np.ndarray, np.ndarray]]) -> Tuple[Csr, List[Csr]]:
+    """Splits k snapshots (edge lists) into the overlap CSR and k exclusive CSRs."""
+    lib = _load()
+    k = len(edge_lists)
+    rows = [_i32(r) for r, _ in edge_lists]
+    cols = [_i32(c) for _, c in edge_lists]
+    for r, c in zip(rows, cols):
+        if r.shape != c.shape or r.ndim != 1:
+            raise ValueError("rows and cols must be 1-D arrays of equal length")
+    nnz = np.array([r.size for r in rows], dtype=np.int64)
+    rp = (ctypes.c_void_p * k)(*[r.ctypes.data for r in rows])
+    cp = (ctypes.c_void_p * k)(*[c.ctypes.data for c in cols])
+    h = lib.pipad_oracle_overlap_create(n, k, nnz.ctypes.data, ctypes.addressof(rp),
+                                        ctypes.addressof(cp))
+    if not h:
+        raise ValueError("oracle rejected the snapshots (index out of range or bad sizes)")
+    try:
+        parts = []
+        for t in range(-1, k):
+            m = lib.pipad_oracle_overlap_nnz(h, t)
+            rowptr = np.empty(n + 1, dtype=np.int32)
+            col = np.empty(m, dtype=np.int32)
+            if lib.pipad_oracle_overlap_csr(h, t, rowptr.ctypes.data, col.ctypes.data) != 0:
+                raise RuntimeError("pipad_oracle_overlap_csr failed")
+            parts.append((rowptr, col))
+    finally:
+        lib.pipad_oracle_overlap_destroy(h)
+    return parts[0], parts[1:]
+
+
+def aggregate(n: int, rows, cols, X: np.ndarray, threads: int = 1, want_bound: bool = True,
+              want_double: bool = True):
+    """Y = D^-1/2 (A+I) D^-1/2 X for one snapshot given as an edge list.
+
+    Returns ``(Y float32[n,F], Yd float64[n,F] | None, B float64[n,F] | None, threads_used)`` where
+    ``B = |A^| |X|`` element-wise is the scale of the parity tolerance."""
+    lib = _load()
+    rows, cols = _i32(rows), _i32(cols)
+    if X.dtype != np.float32 or X.ndim != 2 or X.strides[1] != 4 or X.strides[0] % 4:
+        raise ValueError("X must be a float32 matrix with unit column stride")
+    if X.shape[0] != n:
+        raise ValueError("X must have n rows")
+    F = X.shape[1]
+    ldx = X.strides[0] // 4 if n > 1 else max(F, X.strides[0] // 4)
+    Y = np.empty((n, F), dtype=np.float32)
+    Yd = np.empty((n, F), dtype=np.float64) if want_double else None
+    B = np.empty((n, F), dtype=np.float64) if want_bound else None
+    used = lib.pipad_oracle_aggregate(
+        n, rows.size, rows.ctypes.data, cols.ctypes.data, F, X.ctypes.data, ldx,
+        Y.ctypes.data, F, Yd.ctypes.data if want_double else None,
+        B.ctypes.data if want_bound else None, threads)
+    if used < 1:
+        raise ValueError("oracle rejected the arguments")
+    return Y, Yd, B, used
