@@ -1,0 +1,147 @@
+/* pipad.h - C ABI of the frame-parallel GCN aggregation library for AMD MI355X (gfx950).
+ *
+ * The library implements one thing: neighbour aggregation of a GCN layer over a frame (sliding
+ * window) of k graph snapshots, the way PiPAD's "dimension-aware parallel GNN" organises it
+ * (Section 4.2): the topology of the snapshot group is regrouped as ONE overlap part shared by all
+ * k snapshots plus one exclusive part per snapshot (Section 4.1, "Overlap-aware data transfer");
+ * the overlap part is applied once to the features of all k snapshots (the "coalescent" features),
+ * and every snapshot's exclusive part is applied to its own features and added back.  The result
+ * is, for every snapshot t of the frame,
+ *
+ *      Y_t = D_t^-1/2 (A_t + I) D_t^-1/2  X_t ,      D_t = row sums of (A_t + I)
+ *
+ * (Eq. 1 of Section 2.1 aggregates over N(v) united with {v}; the normalisation is the symmetric
+ * GCN one).  A_t is a 0/1 pattern; self-loops are implicit and never stored.
+ *
+ * Conventions that hold for every call
+ *  - All array arguments named "device" are pointers into GPU memory of the CURRENT HIP device;
+ *    arrays named "host" are ordinary host arrays that only need to live for the duration of the
+ *    call.  The library never copies feature data to the host.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on
+ *    that stream; the caller orders its own work against it.
+ *  - Every function returns 0 (PIPAD_OK) or a negative pipad_status; nothing throws or aborts.
+ *    On failure no output argument is written.
+ *  - Indices are int32.  A snapshot must have fewer than 2^31 stored entries.
+ */
+#ifndef PIPAD_H_
+#define PIPAD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PIPAD_MAX_K 32 /* most snapshots one frame may hold */
+
+typedef enum pipad_status {
+  PIPAD_OK = 0,
+  PIPAD_ERR_INVALID_ARG = -1, /* null pointer, k < 1 or > PIPAD_MAX_K, n < 0, F < 1, ld < F ... */
+  PIPAD_ERR_BAD_CSR = -2,     /* PIPAD_VALIDATE found a snapshot that is not canonical          */
+  PIPAD_ERR_ALLOC = -3,       /* device allocation failed (callback returned NULL / hipMalloc)  */
+  PIPAD_ERR_TOO_LARGE = -4,   /* a size does not fit the int32 index space                      */
+  PIPAD_ERR_HIP = -5          /* a HIP runtime call failed; see pipad_last_hip_error()          */
+} pipad_status;
+
+/* One sparse 0/1 pattern in CSR.  Used for the input snapshots and for borrowed views of a
+ * frame's parts.  Canonical form (required of inputs, guaranteed for outputs):
+ * rowptr[0] == 0, rowptr non-decreasing, rowptr[n] == nnz, column indices in [0, n), strictly
+ * ascending within a row, no diagonal entry. */
+typedef struct pipad_csr {
+  int32_t n;             /* rows == columns == number of nodes          */
+  int32_t nnz;           /* stored entries == rowptr[n]                 */
+  const int32_t *rowptr; /* device, int32[n + 1]                        */
+  const int32_t *colidx; /* device, int32[nnz] (may be NULL when nnz=0) */
+} pipad_csr_t;
+
+/* Opaque frame: overlap CSR + k exclusive CSRs + per-snapshot D^-1/2 + launch metadata. */
+typedef struct pipad_frame pipad_frame_t;
+
+/* Optional device allocator.  Must return memory of at least `bytes` bytes, aligned to 256 bytes,
+ * usable on `stream`'s device, or NULL on failure.  Memory obtained through the callback is owned
+ * by the caller and must stay valid until pipad_frame_destroy(); the library never frees it. */
+typedef void *(*pipad_alloc_fn)(size_t bytes, void *ctx);
+
+#define PIPAD_VALIDATE 1u /* flag: check on the device that every input snapshot is canonical */
+
+/* Overlap extraction (Section 4.1 "Overlap-aware data transfer", Section 4.3 data preparation
+ * module): splits the k snapshots of a frame into
+ *      common  = the directed edges present in every snapshot   (exact set intersection), and
+ *      delta_t = edges of snapshot t that are not in common      (t = 0 .. k-1),
+ * both as canonical CSR, and computes dinv_t[i] = (1 + |row i of A_t|)^-1/2.
+ *
+ *   n       number of nodes (same for all snapshots), n >= 0
+ *   k       snapshots in the frame, 1 <= k <= PIPAD_MAX_K
+ *   snaps   host array of k descriptors whose rowptr/colidx are device arrays; each must have
+ *           snaps[t].n == n.  The inputs are only read and need not outlive the call.
+ *   flags   0 or PIPAD_VALIDATE (costs one extra pass; returns PIPAD_ERR_BAD_CSR on violation;
+ *           without it, non-canonical input gives undefined results but no out-of-range write
+ *           as long as rowptr is a valid offset array into colidx)
+ *   alloc   NULL: the library allocates with hipMalloc and frees in pipad_frame_destroy();
+ *           otherwise every device buffer of the frame is obtained through alloc(bytes, ctx)
+ *   stream  stream the kernels run on.  The call synchronises with it (sizes of the outputs are
+ *           data dependent and are read back once); on return the frame is complete.
+ *   out     receives the new frame.
+ */
+int pipad_frame_build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags,
+                              pipad_alloc_fn alloc, void *alloc_ctx, void *stream,
+                              pipad_frame_t **out);
+
+/* Borrowed views (valid until the frame is destroyed) of the overlap part and of the exclusive
+ * part of snapshot t; see pipad_csr_t for the guarantees. */
+int pipad_frame_common(const pipad_frame_t *frame, pipad_csr_t *view);
+int pipad_frame_delta(const pipad_frame_t *frame, int32_t t, pipad_csr_t *view);
+
+/* Borrowed view of D^-1/2: the value for node i of snapshot t is dinv[i * ld_node + t * ld_snap]
+ * (device, float). */
+int pipad_frame_dinv(const pipad_frame_t *frame, const float **dinv, int64_t *ld_node,
+                     int64_t *ld_snap);
+
+/* Frame size queries: *n, *k as given to build; each may be NULL. */
+int pipad_frame_shape(const pipad_frame_t *frame, int32_t *n, int32_t *k);
+
+/* Frame-parallel aggregation (Section 4.2 "Dimension-aware parallel GNN": parallel aggregation of
+ * the overlap part with the coalescent features plus the per-snapshot aggregations of the
+ * exclusive parts; Eq. 1 for what is aggregated):
+ *
+ *      Y[t][i, 0:F] = dinv_t[i] * ( sum_{j in common(i) U delta_t(i) U {i}} dinv_t[j] * X[t][j, 0:F] )
+ *
+ *   F    feature columns, F >= 1
+ *   X    host array of k device pointers; X[t] is a row-major float matrix, n rows, row stride ldx
+ *        elements (ldx >= F).  Passing X[t] = base + t*F with ldx = k*F hands over the physically
+ *        concatenated (coalescent) operand through the same call.
+ *   Y    host array of k device pointers, row stride ldy >= F; written exactly once per element
+ *        (columns >= F of a wider row are not touched).  Y must not overlap X.
+ *   Only enqueues work on `stream`; no host synchronisation.  The first call with a larger k*F
+ *   than any before may allocate (and keep) a scratch buffer for the partial sums of very long
+ *   rows.  Two aggregations of the SAME frame must not run concurrently (they share that scratch).
+ *   Results are deterministic: same inputs, same bits.
+ */
+int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *const *X,
+                          int64_t ldx, float *const *Y, int64_t ldy, void *stream);
+
+/* Releases the frame and every buffer the library allocated itself.  NULL is allowed. */
+void pipad_frame_destroy(pipad_frame_t *frame);
+
+/* Static text for a status code. */
+const char *pipad_strerror(int status);
+
+/* Text of the last HIP runtime error seen by the calling thread ("" if none). */
+const char *pipad_last_hip_error(void);
+
+/* Kernel-selection knobs for measurements; process-wide, not thread-safe.  Unknown keys return
+ * PIPAD_ERR_INVALID_ARG.  Keys:
+ *   "agg_variant"  0 = automatic; 1 = one wave covers all k snapshots of a row (coalescent row);
+ *                  2 = one snapshot per workgroup column, snapshots spread over workgroups
+ *   "hub_threshold"  rows with more than this many (common + longest exclusive) entries are
+ *                    split into segments; takes effect for frames built afterwards
+ *   "hub_segment"    entries per segment of a split row; takes effect for frames built afterwards
+ */
+int pipad_set_option(const char *key, int64_t value);
+int pipad_get_option(const char *key, int64_t *value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPAD_H_ */

@@ -1,0 +1,268 @@
+"""Thin ctypes binding of libpipad.so: argument marshalling only.
+
+Every step of the path (overlap extraction, normalisation, aggregation) runs in the HIP kernels of
+the library; nothing here computes.  PyTorch supplies device memory and streams.  There is no CPU
+fallback: if the library cannot be loaded the import of this module's functions fails loudly.
+
+The names mirror ``include/pipad.h``:
+  pipad_frame_build_overlap  -> :func:`frame_build_overlap`   (Section 4.1 / 4.3: overlap + exclusive parts)
+  pipad_frame_aggregate      -> :func:`frame_aggregate`       (Section 4.2: parallel + exclusive aggregation)
+  pipad_frame_common / _delta / _dinv -> :meth:`Frame.common`, :meth:`Frame.delta`, :meth:`Frame.dinv`
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple, Union
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpipad.so")
+MAX_K = 32
+VALIDATE = 1
+
+_lib = None
+
+
+class PipadError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libpipad: {text} (status {status})")
+        self.status = status
+
+
+class _Csr(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int32), ("nnz", ctypes.c_int32),
+                ("rowptr", ctypes.c_void_p), ("colidx", ctypes.c_void_p)]
+
+
+ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
+
+# symbol -> (restype, argtypes); also the list the ABI test checks against include/pipad.h
+_vp, _i32, _i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+SIGNATURES = {
+    "pipad_frame_build_overlap": (ctypes.c_int, [_i32, _i32, ctypes.POINTER(_Csr), ctypes.c_uint32,
+                                                 _vp, _vp, _vp, ctypes.POINTER(_vp)]),
+    "pipad_frame_common": (ctypes.c_int, [_vp, ctypes.POINTER(_Csr)]),
+    "pipad_frame_delta": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_Csr)]),
+    "pipad_frame_dinv": (ctypes.c_int, [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_i64),
+                                        ctypes.POINTER(_i64)]),
+    "pipad_frame_shape": (ctypes.c_int, [_vp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]),
+    "pipad_frame_aggregate": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_vp), _i64,
+                                             ctypes.POINTER(_vp), _i64, _vp]),
+    "pipad_frame_destroy": (None, [_vp]),
+    "pipad_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "pipad_last_hip_error": (ctypes.c_char_p, []),
+    "pipad_set_option": (ctypes.c_int, [ctypes.c_char_p, _i64]),
+    "pipad_get_option": (ctypes.c_int, [ctypes.c_char_p, ctypes.POINTER(_i64)]),
+}
+
+
+def load_library():
+    """Loads libpipad.so (building it first only if it does not exist yet)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        lib = load_library()
+        text = lib.pipad_strerror(status).decode()
+        if status == -5:
+            text += ": " + lib.pipad_last_hip_error().decode()
+        raise PipadError(status, text)
+
+
+def set_option(key: str, value: int) -> None:
+    _check(load_library().pipad_set_option(key.encode(), int(value)))
+
+
+def get_option(key: str) -> int:
+    v = _i64(0)
+    _check(load_library().pipad_get_option(key.encode(), ctypes.byref(v)))
+    return int(v.value)
+
+
+class _DevArray:
+    """Exposes a raw device pointer through __cuda_array_interface__ (view, copied at once by the caller)."""
+
+    def __init__(self, ptr: int, count: int, typestr: str):
+        self.__cuda_array_interface__ = {"shape": (count,), "typestr": typestr,
+                                         "data": (ptr, False), "version": 2}
+
+
+def _copy_from_device(ptr: Optional[int], count: int, dtype: torch.dtype, device) -> torch.Tensor:
+    if count == 0 or not ptr:
+        return torch.empty(0, dtype=dtype, device=device)
+    typestr = {torch.int32: "<i4", torch.float32: "<f4"}[dtype]
+    return torch.as_tensor(_DevArray(ptr, count, typestr), device=device).clone()
+
+
+def _stream_handle(stream) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+Snapshot = Tuple[torch.Tensor, torch.Tensor]  # (rowptr int32[n+1], colidx int32[nnz]) on the GPU
+
+
+class Frame:
+    """Owner of one ``pipad_frame_t``.  Built by :func:`frame_build_overlap`."""
+
+    def __init__(self, handle: int, n: int, k: int, device, buffers: list):
+        self._h = handle
+        self.n, self.k, self.device = n, k, device
+        self._buffers = buffers  # torch tensors handed to the library through the allocator
+
+    def close(self) -> None:
+        if self._h:
+            load_library().pipad_frame_destroy(self._h)
+            self._h = None
+            self._buffers = []
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _view(self, t: Optional[int]) -> Tuple[torch.Tensor, torch.Tensor]:
+        lib = load_library()
+        v = _Csr()
+        if t is None:
+            _check(lib.pipad_frame_common(self._h, ctypes.byref(v)))
+        else:
+            _check(lib.pipad_frame_delta(self._h, t, ctypes.byref(v)))
+        torch.cuda.synchronize(self.device)
+        rowptr = _copy_from_device(v.rowptr, self.n + 1, torch.int32, self.device)
+        col = _copy_from_device(v.colidx, v.nnz, torch.int32, self.device)
+        return rowptr, col
+
+    def common(self) -> Snapshot:
+        """Copy of the overlap CSR (pipad_frame_common)."""
+        return self._view(None)
+
+    def delta(self, t: int) -> Snapshot:
+        """Copy of the exclusive CSR of snapshot t (pipad_frame_delta)."""
+        return self._view(t)
+
+    def dinv(self) -> torch.Tensor:
+        """Copy of D^-1/2 as a float32[k, n] tensor (pipad_frame_dinv)."""
+        lib = load_library()
+        ptr, ldn, lds = _vp(), _i64(), _i64()
+        _check(lib.pipad_frame_dinv(self._h, ctypes.byref(ptr), ctypes.byref(ldn), ctypes.byref(lds)))
+        assert ldn.value == 1 and lds.value == self.n
+        torch.cuda.synchronize(self.device)
+        return _copy_from_device(ptr.value, self.k * self.n, torch.float32, self.device).view(self.k, self.n)
+
+
+def frame_build_overlap(snapshots: Sequence[Snapshot], validate: bool = False,
+                        allocator: str = "torch", stream=None) -> Frame:
+    """pipad_frame_build_overlap: k CSR snapshots -> frame (overlap CSR + k exclusive CSRs + D^-1/2).
+
+    ``allocator="torch"`` hands every frame buffer out of PyTorch's caching allocator through the
+    C callback; ``"library"`` lets the library hipMalloc its own."""
+    lib = load_library()
+    k = len(snapshots)
+    if k < 1:
+        raise ValueError("a frame needs at least one snapshot")
+    rp0 = snapshots[0][0]
+    n = rp0.numel() - 1
+    device = rp0.device
+    arr = (_Csr * k)()
+    keep = []
+    for t, (rp, col) in enumerate(snapshots):
+        for x in (rp, col):
+            if x.dtype != torch.int32 or not x.is_cuda or not x.is_contiguous() or x.device != device:
+                raise ValueError("snapshots must be contiguous int32 tensors on one GPU")
+        keep.append((rp, col))
+        arr[t].n = rp.numel() - 1
+        arr[t].nnz = col.numel()
+        arr[t].rowptr = rp.data_ptr()
+        arr[t].colidx = col.data_ptr() if col.numel() else None
+    buffers: list = []
+    cb = None
+    failed = []
+    if allocator == "torch":
+        def _alloc(nbytes, _ctx):
+            try:
+                buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+                buffers.append(buf)
+                return buf.data_ptr()
+            except Exception as exc:  # out of memory -> NULL -> PIPAD_ERR_ALLOC
+                failed.append(exc)
+                return None
+        cb = ALLOC_FN(_alloc)
+    elif allocator != "library":
+        raise ValueError("allocator must be 'torch' or 'library'")
+    out = _vp()
+    with torch.cuda.device(device):
+        status = lib.pipad_frame_build_overlap(
+            n, k, arr, VALIDATE if validate else 0,
+            ctypes.cast(cb, _vp) if cb is not None else None, None,
+            _stream_handle(stream), ctypes.byref(out))
+    _check(status)
+    return Frame(out.value, n, k, device, buffers)
+
+
+Features = Union[torch.Tensor, Sequence[torch.Tensor]]
+
+
+def _operand(x: Features, n: int, k: int, name: str) -> Tuple[List[int], int, int]:
+    """Returns (k device pointers, row stride in elements, F).  Accepts a list of k [n, F] matrices
+    sharing one row stride, or one [n, k, F] tensor (the physically concatenated coalescent operand)."""
+    if isinstance(x, torch.Tensor):
+        if x.dim() != 3 or x.shape[0] != n or x.shape[1] != k:
+            raise ValueError(f"{name}: a single tensor must have shape [n, k, F]")
+        mats = [x[:, t, :] for t in range(k)]
+    else:
+        mats = list(x)
+        if len(mats) != k:
+            raise ValueError(f"{name}: need k = {k} matrices")
+    F = mats[0].shape[1]
+    ld = None
+    ptrs = []
+    for m in mats:
+        if m.dtype != torch.float32 or not m.is_cuda or m.dim() != 2 or tuple(m.shape) != (n, F):
+            raise ValueError(f"{name}: every matrix must be float32 [n, F] on the GPU")
+        if F > 1 and m.stride(1) != 1:
+            raise ValueError(f"{name}: feature columns must be contiguous")
+        row = m.stride(0) if n > 1 else max(m.stride(0), F)
+        if ld is None:
+            ld = row
+        elif n > 1 and row != ld:
+            raise ValueError(f"{name}: all matrices must share one row stride")
+        ptrs.append(m.data_ptr())
+    return ptrs, int(ld), int(F)
+
+
+def frame_aggregate(frame: Frame, X: Features, Y: Optional[Features] = None, stream=None) -> Features:
+    """pipad_frame_aggregate: Y_t = D_t^-1/2 (A_t + I) D_t^-1/2 X_t for every snapshot of the frame.
+
+    Y is allocated like X when not given.  Only enqueues work on the stream."""
+    lib = load_library()
+    n, k = frame.n, frame.k
+    xp, ldx, F = _operand(X, n, k, "X")
+    if Y is None:
+        if isinstance(X, torch.Tensor):
+            Y = torch.empty_like(X, memory_format=torch.contiguous_format)
+        else:
+            Y = [torch.empty((n, F), dtype=torch.float32, device=frame.device) for _ in range(k)]
+    yp, ldy, Fy = _operand(Y, n, k, "Y")
+    if Fy != F:
+        raise ValueError("X and Y must have the same number of feature columns")
+    xa = (_vp * k)(*xp)
+    ya = (_vp * k)(*yp)
+    with torch.cuda.device(frame.device):
+        _check(lib.pipad_frame_aggregate(frame._h, F, xa, ldx, ya, ldy, _stream_handle(stream)))
+    return Y

@@ -1,0 +1,136 @@
+// C ABI of libpipad: argument checks and dispatch.  See include/pipad.h for the contract.
+#include <cstdio>
+#include <cstring>
+#include <string>
+
+#include "pipad_internal.h"
+
+namespace pipad {
+
+static thread_local std::string g_hip_error;
+
+int hip_fail(hipError_t e, const char *what) {
+  g_hip_error = std::string(hipGetErrorString(e)) + " in " + what;
+  (void)hipGetLastError();  // clear the sticky error so that later calls are not blamed
+  return PIPAD_ERR_HIP;
+}
+
+Options &options() {
+  static Options o;
+  return o;
+}
+
+int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags,
+                  pipad_alloc_fn alloc, void *alloc_ctx, hipStream_t st, pipad_frame **out);
+void destroy_frame(pipad_frame *f);
+
+}  // namespace pipad
+
+extern "C" {
+
+int pipad_frame_build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags,
+                              pipad_alloc_fn alloc, void *alloc_ctx, void *stream,
+                              pipad_frame_t **out) {
+  if (!out || !snaps || n < 0 || k < 1 || k > PIPAD_MAX_K) return PIPAD_ERR_INVALID_ARG;
+  if (flags & ~PIPAD_VALIDATE) return PIPAD_ERR_INVALID_ARG;
+  for (int t = 0; t < k; ++t) {
+    if (snaps[t].n != n || snaps[t].nnz < 0 || !snaps[t].rowptr) return PIPAD_ERR_INVALID_ARG;
+    if (snaps[t].nnz > 0 && !snaps[t].colidx) return PIPAD_ERR_INVALID_ARG;
+    if (n == 0 && snaps[t].nnz != 0) return PIPAD_ERR_INVALID_ARG;
+  }
+  pipad_frame *f = nullptr;
+  const int rc = pipad::build_overlap(n, k, snaps, flags, alloc, alloc_ctx,
+                                      static_cast<hipStream_t>(stream), &f);
+  if (rc != PIPAD_OK) return rc;
+  *out = f;
+  return PIPAD_OK;
+}
+
+int pipad_frame_common(const pipad_frame_t *f, pipad_csr_t *view) {
+  if (!f || !view) return PIPAD_ERR_INVALID_ARG;
+  view->n = f->n;
+  view->nnz = f->nnz_c;
+  view->rowptr = f->rowptr_c;
+  view->colidx = f->col_c;
+  return PIPAD_OK;
+}
+
+int pipad_frame_delta(const pipad_frame_t *f, int32_t t, pipad_csr_t *view) {
+  if (!f || !view || t < 0 || t >= f->k) return PIPAD_ERR_INVALID_ARG;
+  view->n = f->n;
+  view->nnz = f->nnz_d[t];
+  view->rowptr = f->rowptr_d[t];
+  view->colidx = f->col_d[t];
+  return PIPAD_OK;
+}
+
+int pipad_frame_dinv(const pipad_frame_t *f, const float **dinv, int64_t *ld_node,
+                     int64_t *ld_snap) {
+  if (!f || !dinv || !ld_node || !ld_snap) return PIPAD_ERR_INVALID_ARG;
+  *dinv = f->dinv;
+  *ld_node = 1;
+  *ld_snap = f->n;
+  return PIPAD_OK;
+}
+
+int pipad_frame_shape(const pipad_frame_t *f, int32_t *n, int32_t *k) {
+  if (!f) return PIPAD_ERR_INVALID_ARG;
+  if (n) *n = f->n;
+  if (k) *k = f->k;
+  return PIPAD_OK;
+}
+
+int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *const *X,
+                          int64_t ldx, float *const *Y, int64_t ldy, void *stream) {
+  if (!frame || !X || !Y || F < 1 || ldx < F || ldy < F) return PIPAD_ERR_INVALID_ARG;
+  if (frame->n > 0)
+    for (int t = 0; t < frame->k; ++t)
+      if (!X[t] || !Y[t]) return PIPAD_ERR_INVALID_ARG;
+  if ((int64_t)frame->n * ldx >= ((int64_t)1 << 40) || (int64_t)frame->n * ldy >= ((int64_t)1 << 40))
+    return PIPAD_ERR_TOO_LARGE;
+  // the frame's scratch buffer is the only mutable state
+  return pipad::aggregate_launch(const_cast<pipad_frame *>(frame), F, X, ldx, Y, ldy,
+                                 static_cast<hipStream_t>(stream));
+}
+
+void pipad_frame_destroy(pipad_frame_t *frame) { pipad::destroy_frame(frame); }
+
+const char *pipad_strerror(int status) {
+  switch (status) {
+    case PIPAD_OK: return "ok";
+    case PIPAD_ERR_INVALID_ARG: return "invalid argument";
+    case PIPAD_ERR_BAD_CSR: return "snapshot is not a canonical CSR pattern";
+    case PIPAD_ERR_ALLOC: return "device allocation failed";
+    case PIPAD_ERR_TOO_LARGE: return "size exceeds the int32 index space";
+    case PIPAD_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char *pipad_last_hip_error(void) { return pipad::g_hip_error.c_str(); }
+
+static int64_t *option_slot(const char *key) {
+  pipad::Options &o = pipad::options();
+  if (!key) return nullptr;
+  if (!std::strcmp(key, "agg_variant")) return &o.agg_variant;
+  if (!std::strcmp(key, "agg_rowslots")) return &o.agg_rowslots;
+  if (!std::strcmp(key, "hub_threshold")) return &o.hub_threshold;
+  if (!std::strcmp(key, "hub_segment")) return &o.hub_segment;
+  return nullptr;
+}
+
+int pipad_set_option(const char *key, int64_t value) {
+  int64_t *slot = option_slot(key);
+  if (!slot || value < 0) return PIPAD_ERR_INVALID_ARG;
+  *slot = value;
+  return PIPAD_OK;
+}
+
+int pipad_get_option(const char *key, int64_t *value) {
+  int64_t *slot = option_slot(key);
+  if (!slot || !value) return PIPAD_ERR_INVALID_ARG;
+  *value = *slot;
+  return PIPAD_OK;
+}
+
+}  // extern "C"

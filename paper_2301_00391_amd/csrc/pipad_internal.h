@@ -1,0 +1,74 @@
+// Internal declarations shared by the translation units of libpipad (never installed).
+#ifndef PIPAD_INTERNAL_H_
+#define PIPAD_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "pipad.h"
+
+namespace pipad {
+
+constexpr int kWave = 64;        // gfx950 wavefront width
+constexpr int kBlock = 256;      // threads per workgroup used by every kernel here (4 waves)
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+// Records the text of a failed HIP call for pipad_last_hip_error() and returns PIPAD_ERR_HIP.
+int hip_fail(hipError_t e, const char *what);
+
+#define PIPAD_HIP(call)                                            \
+  do {                                                             \
+    hipError_t e__ = (call);                                       \
+    if (e__ != hipSuccess) return ::pipad::hip_fail(e__, #call);   \
+  } while (0)
+
+struct Options {
+  int64_t agg_variant = 0;     // 0 auto, 1 coalescent row per wave, 2 one snapshot per unit
+  int64_t agg_rowslots = 0;    // 1: idle lane groups of a wave take further rows, not further edges
+  int64_t hub_threshold = 512; // rows longer than this are split into segments
+  int64_t hub_segment = 256;   // entries per segment
+};
+Options &options();
+
+}  // namespace pipad
+
+// The frame.  All pointers are device pointers on `device`.
+struct pipad_frame {
+  int32_t n = 0, k = 0;
+  int device = 0;
+  bool own_memory = true;            // buffers came from hipMalloc (freed in destroy)
+  std::vector<void *> owned;         // everything to hipFree when own_memory
+
+  int32_t nnz_c = 0;
+  int32_t *rowptr_c = nullptr;       // [n+1]
+  int32_t *col_c = nullptr;          // [nnz_c]
+  int32_t nnz_d[PIPAD_MAX_K] = {};
+  int32_t *rowptr_d[PIPAD_MAX_K] = {};  // each [n+1]
+  int32_t *col_d[PIPAD_MAX_K] = {};     // each [nnz_d[t]]
+  float *dinv = nullptr;             // [k][n]: dinv[t*n + i]
+
+  // Long ("hub") rows: rows whose common + longest exclusive length exceeds hub_threshold are cut
+  // into segments of hub_segment entries; every segment is one work item.
+  int32_t hub_threshold = 0, hub_segment = 0;
+  uint8_t *rowclass = nullptr;       // [n]: 1 = hub row
+  int32_t n_hub = 0;
+  int32_t *hub_rows = nullptr;       // [n_hub] ascending row ids
+  int32_t *hub_item_off = nullptr;   // [n_hub+1] first item of each hub row
+  int32_t n_items = 0;
+  int32_t *item_row = nullptr;       // [n_items]
+  int32_t *item_seg = nullptr;       // [n_items] segment number within its row
+
+  // Scratch for the partial sums of hub segments: n_items * k * F floats, grown on demand.
+  float *partial = nullptr;
+  size_t partial_floats = 0;
+};
+
+namespace pipad {
+int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t ldx,
+                     float *const *Y, int64_t ldy, hipStream_t stream);
+}
+
+#endif  // PIPAD_INTERNAL_H_

@@ -1,0 +1,248 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Integer outputs (overlap and exclusive CSRs) must be bit-exact; fp32 outputs must satisfy
+|dY| <= 1e-5 * (|A^| |X|) per element.  Inputs are the seeded synthetic frames of ``synth``.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from _util import check_overlap, check_y, csr_to_coo, to_gpu_snapshots
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def pipad():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2301_00391_amd as p
+    p.load_library()
+    return p
+
+
+@pytest.fixture(autouse=True)
+def _reset_options(pipad):
+    yield
+    for key, val in (("agg_variant", 0), ("agg_rowslots", 0), ("hub_threshold", 512),
+                     ("hub_segment", 256)):
+        pipad.set_option(key, val)
+
+
+def run_case(pipad, n, lists, F, seed, layout="list", allocator="torch", validate=True,
+             check_csr=True):
+    """lists: k (rowptr, col) numpy CSR pairs.  Returns the worst error ratio."""
+    k = len(lists)
+    dev = "cuda:0"
+    snaps = [(torch.from_numpy(np.ascontiguousarray(rp)).to(dev),
+              torch.from_numpy(np.ascontiguousarray(c)).to(dev)) for rp, c in lists]
+    frame = pipad.frame_build_overlap(snaps, validate=validate, allocator=allocator)
+    coo = [csr_to_coo(n, rp, c) for rp, c in lists]
+    if check_csr:
+        check_overlap(frame, oracle.overlap(n, coo))
+    X = [synth.features(seed, t, n, F) for t in range(k)]
+    if layout == "wide":
+        xw = torch.from_numpy(np.stack(X, axis=1)).to(dev)  # [n, k, F]
+        yw = pipad.frame_aggregate(frame, xw)
+        torch.cuda.synchronize()
+        ys = [yw[:, t, :].cpu().numpy() for t in range(k)]
+    else:
+        xs = [torch.from_numpy(x).to(dev) for x in X]
+        yl = pipad.frame_aggregate(frame, xs)
+        torch.cuda.synchronize()
+        ys = [y.cpu().numpy() for y in yl]
+    worst = 0.0
+    for t in range(k):
+        _, yd, bound, _ = oracle.aggregate(n, coo[t][0], coo[t][1], X[t], threads=8)
+        worst = max(worst, check_y(ys[t], yd, bound, f"snapshot {t}"))
+    frame.close()
+    return worst
+
+
+def rand_csr(rng, n, p, symmetric=True):
+    M = rng.random((n, n)) < p
+    if symmetric:
+        M = np.triu(M, 1)
+        M = M | M.T
+    np.fill_diagonal(M, False)
+    rowptr = np.concatenate([[0], np.cumsum(M.sum(axis=1))]).astype(np.int32)
+    col = np.nonzero(M)[1].astype(np.int32)
+    return rowptr, col
+
+
+def churned(rng, n, k, p, keep, symmetric=True):
+    base = rng.random((n, n)) < p
+    out = []
+    for _ in range(k):
+        M = base & (rng.random((n, n)) < keep) | (rng.random((n, n)) < p * (1 - keep))
+        if symmetric:
+            M = np.triu(M, 1)
+            M = M | M.T
+        np.fill_diagonal(M, False)
+        rowptr = np.concatenate([[0], np.cumsum(M.sum(axis=1))]).astype(np.int32)
+        out.append((rowptr, np.nonzero(M)[1].astype(np.int32)))
+    return out
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("layout", ["list", "wide"])
+def test_tiny_config(pipad, variant, layout):
+    pipad.set_option("agg_variant", variant)
+    cfg = synth.CONFIGS["tiny"]
+    s = synth.make(cfg)
+    lists = [(s.rowptr[t], s.col[t]) for t in range(cfg.k)]
+    run_case(pipad, cfg.n, lists, cfg.feat, cfg.seed, layout=layout)
+
+
+@pytest.mark.parametrize("first", [0, 7, 12])
+def test_small_config_sliding_frames(pipad, first):
+    cfg = synth.CONFIGS["small"]
+    s = synth.make(cfg)
+    lists = [(s.rowptr[t], s.col[t]) for t in range(first, first + cfg.k)]
+    run_case(pipad, cfg.n, lists, cfg.feat, cfg.seed + first, layout="wide")
+
+
+@pytest.mark.parametrize("k,F", [(1, 1), (2, 2), (3, 6), (4, 16), (5, 20), (8, 64), (8, 128),
+                                 (2, 130), (16, 32), (3, 260), (32, 4), (8, 256), (7, 12)])
+@pytest.mark.parametrize("variant", [1, 2])
+def test_shapes_and_feature_widths(pipad, k, F, variant):
+    pipad.set_option("agg_variant", variant)
+    rng = np.random.default_rng(1000 * k + F)
+    n = 333  # several workgroups and a ragged tail
+    lists = churned(rng, n, k, 0.03, 0.8)
+    run_case(pipad, n, lists, F, seed=k * 7 + F, layout="wide" if F % 2 == 0 else "list")
+
+
+@pytest.mark.parametrize("variant,rowslots", [(1, 0), (2, 0), (2, 1), (1, 1)])
+def test_hub_rows_are_split_and_rowslots(pipad, variant, rowslots):
+    """Low hub threshold: most rows take the segmented path (partials + fixed-order reduction)."""
+    pipad.set_option("agg_variant", variant)
+    pipad.set_option("agg_rowslots", rowslots)
+    pipad.set_option("hub_threshold", 6)
+    pipad.set_option("hub_segment", 4)
+    rng = np.random.default_rng(77)
+    n = 500
+    lists = churned(rng, n, 4, 0.04, 0.7)
+    run_case(pipad, n, lists, 16, seed=5)
+    run_case(pipad, n, lists, 9, seed=6)
+
+
+def test_directed_patterns(pipad):
+    rng = np.random.default_rng(5)
+    lists = churned(rng, 257, 3, 0.05, 0.6, symmetric=False)
+    run_case(pipad, 257, lists, 24, seed=11)
+
+
+def test_degenerate_frames(pipad):
+    rng = np.random.default_rng(6)
+    n = 130
+    a = rand_csr(rng, n, 0.05)
+    empty = (np.zeros(n + 1, np.int32), np.zeros(0, np.int32))
+    # k = 1: all common; identical snapshots: no exclusive edges
+    run_case(pipad, n, [a], 8, seed=1)
+    run_case(pipad, n, [a, a, a], 8, seed=2)
+    # one empty snapshot: empty overlap, everything exclusive; all empty: Y = X
+    run_case(pipad, n, [a, empty], 8, seed=3)
+    run_case(pipad, n, [empty, a], 8, seed=3)
+    run_case(pipad, n, [empty, empty], 8, seed=4)
+    # a single node, and two nodes joined by an edge
+    run_case(pipad, 1, [(np.zeros(2, np.int32), np.zeros(0, np.int32))], 4, seed=5)
+    two = (np.array([0, 1, 2], np.int32), np.array([1, 0], np.int32))
+    run_case(pipad, 2, [two, two], 4, seed=6)
+
+
+def test_no_nodes(pipad):
+    rp = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    col = torch.zeros(0, dtype=torch.int32, device="cuda:0")
+    frame = pipad.frame_build_overlap([(rp, col), (rp, col)])
+    c_rp, c_col = frame.common()
+    assert c_rp.tolist() == [0] and c_col.numel() == 0
+    x = torch.zeros((0, 2, 4), device="cuda:0")
+    y = pipad.frame_aggregate(frame, x)
+    assert y.shape == (0, 2, 4)
+
+
+def test_library_allocator_and_determinism(pipad):
+    rng = np.random.default_rng(8)
+    n = 400
+    lists = churned(rng, n, 4, 0.03, 0.8)
+    run_case(pipad, n, lists, 32, seed=9, allocator="library")
+    pipad.set_option("hub_threshold", 8)
+    pipad.set_option("hub_segment", 8)
+    snaps = [(torch.from_numpy(rp).cuda(), torch.from_numpy(c).cuda()) for rp, c in lists]
+    frame = pipad.frame_build_overlap(snaps)
+    x = torch.rand((n, 4, 32), device="cuda:0") * 2 - 1
+    y1 = pipad.frame_aggregate(frame, x).clone()
+    y2 = pipad.frame_aggregate(frame, x)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2), "same inputs must give the same bits"
+
+
+def test_padded_rows_are_left_alone(pipad):
+    """ldy > F: the columns beyond F of Y keep their contents."""
+    rng = np.random.default_rng(10)
+    n, k, F, pad = 200, 2, 12, 20
+    lists = churned(rng, n, k, 0.05, 0.8)
+    snaps = [(torch.from_numpy(rp).cuda(), torch.from_numpy(c).cuda()) for rp, c in lists]
+    frame = pipad.frame_build_overlap(snaps)
+    xb = [torch.rand((n, pad), device="cuda:0") for _ in range(k)]
+    yb = [torch.full((n, pad), 7.0, device="cuda:0") for _ in range(k)]
+    pipad.frame_aggregate(frame, [x[:, :F] for x in xb], [y[:, :F] for y in yb])
+    torch.cuda.synchronize()
+    for t in range(k):
+        assert torch.all(yb[t][:, F:] == 7.0)
+        rows, cols = csr_to_coo(n, *lists[t])
+        xnp = np.ascontiguousarray(xb[t][:, :F].cpu().numpy())
+        _, yd, bound, _ = oracle.aggregate(n, rows, cols, xnp)
+        check_y(yb[t][:, :F].cpu().numpy(), yd, bound, f"padded {t}")
+
+
+def test_validation_rejects_non_canonical_input(pipad):
+    n = 50
+    good = rand_csr(np.random.default_rng(12), n, 0.1)
+
+    def build(rp, col):
+        snaps = [(torch.from_numpy(np.asarray(rp, np.int32)).cuda(),
+                  torch.from_numpy(np.asarray(col, np.int32)).cuda())]
+        return pipad.frame_build_overlap(snaps, validate=True)
+
+    build(*good).close()
+    rp, col = good
+    row = int(np.argmax(np.diff(rp) >= 2))
+    a = rp[row]
+    bad_sets = []
+    c = col.copy(); c[a], c[a + 1] = c[a + 1], c[a]; bad_sets.append((rp, c))        # unsorted
+    c = col.copy(); c[a + 1] = c[a]; bad_sets.append((rp, c))                         # duplicate
+    c = col.copy(); c[a] = row; bad_sets.append((rp, c))                              # diagonal
+    c = col.copy(); c[a] = n; bad_sets.append((rp, c))                                # out of range
+    r = rp.copy(); r[3] = r[4] + 1; bad_sets.append((r, col))                         # decreasing
+    r = rp.copy(); r[-1] -= 1; bad_sets.append((r, col))                              # rowptr[n] != nnz
+    for rp_b, col_b in bad_sets:
+        with pytest.raises(pipad.PipadError) as info:
+            build(rp_b, col_b)
+        assert info.value.status == -2
+
+
+def test_invalid_arguments(pipad):
+    rp = torch.zeros(5, dtype=torch.int32, device="cuda:0")
+    col = torch.zeros(0, dtype=torch.int32, device="cuda:0")
+    frame = pipad.frame_build_overlap([(rp, col)])
+    x = torch.zeros((4, 1, 8), device="cuda:0")
+    with pytest.raises(ValueError):
+        pipad.frame_aggregate(frame, torch.zeros((4, 2, 8), device="cuda:0"))
+    with pytest.raises(pipad.PipadError):
+        pipad.frame_build_overlap([(rp, col), (torch.zeros(7, dtype=torch.int32, device="cuda:0"), col)])
+    pipad.frame_aggregate(frame, x)
+    torch.cuda.synchronize()
+
+
+def test_medium_frame_full_check(pipad):
+    """One frame of the medium workload (N = 200k, k = 8, F = 64), every element checked."""
+    cfg = synth.CONFIGS["medium"]
+    s = synth.graphs(cfg.n, cfg.edges, cfg.k, cfg.churn, cfg.model, cfg.params, cfg.seed)
+    lists = [(s.rowptr[t], s.col[t]) for t in range(cfg.k)]
+    worst = run_case(pipad, cfg.n, lists, cfg.feat, cfg.seed, layout="wide", validate=False)
+    print(f"medium worst error ratio {worst:.3e} of the 1e-5 budget")
