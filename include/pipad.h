@@ -60,7 +60,9 @@ typedef struct pipad_frame pipad_frame_t;
 
 /* Optional device allocator.  Must return memory of at least `bytes` bytes, aligned to 256 bytes,
  * usable on `stream`'s device, or NULL on failure.  Memory obtained through the callback is owned
- * by the caller and must stay valid until pipad_frame_destroy(); the library never frees it. */
+ * by the caller and must stay valid until pipad_frame_destroy(); the library never frees it.  The
+ * callback and its ctx must stay callable until then too: besides the frame's own buffers it
+ * serves the temporaries of the build and the scratch buffer of pipad_frame_aggregate. */
 typedef void *(*pipad_alloc_fn)(size_t bytes, void *ctx);
 
 #define PIPAD_VALIDATE 1u /* flag: check on the device that every input snapshot is canonical */
@@ -79,9 +81,12 @@ typedef void *(*pipad_alloc_fn)(size_t bytes, void *ctx);
  *           without it, non-canonical input gives undefined results but no out-of-range write
  *           as long as rowptr is a valid offset array into colidx)
  *   alloc   NULL: the library allocates with hipMalloc and frees in pipad_frame_destroy();
- *           otherwise every device buffer of the frame is obtained through alloc(bytes, ctx)
- *   stream  stream the kernels run on.  The call synchronises with it (sizes of the outputs are
- *           data dependent and are read back once); on return the frame is complete.
+ *           otherwise every device buffer is obtained through alloc(bytes, ctx) and no
+ *           hipMalloc / hipFree is issued
+ *   stream  stream the kernels run on.  The call synchronises with it once (sizes of the outputs
+ *           are data dependent and are read back).  With alloc == NULL the frame is complete on
+ *           return; with a callback the last kernels may still be running on `stream`, so the
+ *           inputs must stay valid, and the frame is used, in stream order.
  *   out     receives the new frame.
  */
 int pipad_frame_build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags,
@@ -132,6 +137,8 @@ const char *pipad_last_hip_error(void);
 
 /* Kernel-selection knobs for measurements; process-wide, not thread-safe.  Unknown keys return
  * PIPAD_ERR_INVALID_ARG.  Keys:
+ *   "agg_rowslots" 1 = spare lane groups of a wave take further rows instead of further
+ *                  entries of the same row
  *   "agg_variant"  0 = automatic; 1 = one wave covers all k snapshots of a row (coalescent row);
  *                  2 = one snapshot per workgroup column, snapshots spread over workgroups
  *   "hub_threshold"  rows with more than this many (common + longest exclusive) entries are

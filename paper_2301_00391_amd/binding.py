@@ -119,10 +119,11 @@ Snapshot = Tuple[torch.Tensor, torch.Tensor]  # (rowptr int32[n+1], colidx int32
 class Frame:
     """Owner of one ``pipad_frame_t``.  Built by :func:`frame_build_overlap`."""
 
-    def __init__(self, handle: int, n: int, k: int, device, buffers: list):
+    def __init__(self, handle: int, n: int, k: int, device, buffers: list, callback=None):
         self._h = handle
         self.n, self.k, self.device = n, k, device
         self._buffers = buffers  # torch tensors handed to the library through the allocator
+        self._callback = callback  # the library may call it again (aggregate scratch)
 
     def close(self) -> None:
         if self._h:
@@ -212,7 +213,7 @@ def frame_build_overlap(snapshots: Sequence[Snapshot], validate: bool = False,
             ctypes.cast(cb, _vp) if cb is not None else None, None,
             _stream_handle(stream), ctypes.byref(out))
     _check(status)
-    return Frame(out.value, n, k, device, buffers)
+    return Frame(out.value, n, k, device, buffers, cb)
 
 
 Features = Union[torch.Tensor, Sequence[torch.Tensor]]

@@ -385,15 +385,21 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   // scratch for hub partial sums
   const size_t need = (size_t)f->n_items * (size_t)f->k * (size_t)F;
   if (need > f->partial_floats) {
-    // the old buffer may still be in use by earlier work on another stream of the caller
-    PIPAD_HIP(hipDeviceSynchronize());
-    if (f->partial) (void)hipFree(f->partial);
-    f->partial = nullptr;
-    f->partial_floats = 0;
     void *ptr = nullptr;
-    if (hipMalloc(&ptr, need * sizeof(float)) != hipSuccess) {
-      (void)hipGetLastError();
-      return PIPAD_ERR_ALLOC;
+    if (f->alloc) {
+      // the caller's allocator owns the memory; a smaller buffer from before stays with it
+      ptr = f->alloc(need * sizeof(float), f->alloc_ctx);
+      if (!ptr) return PIPAD_ERR_ALLOC;
+    } else {
+      // the old buffer may still be in use by earlier work on another stream of the caller
+      PIPAD_HIP(hipDeviceSynchronize());
+      if (f->partial) (void)hipFree(f->partial);
+      f->partial = nullptr;
+      f->partial_floats = 0;
+      if (hipMalloc(&ptr, need * sizeof(float)) != hipSuccess) {
+        (void)hipGetLastError();
+        return PIPAD_ERR_ALLOC;
+      }
     }
     f->partial = static_cast<float *>(ptr);
     f->partial_floats = need;

@@ -322,7 +322,7 @@ void release(pipad_frame *f) {
   if (!f) return;
   if (f->own_memory)
     for (void *ptr : f->owned) (void)hipFree(ptr);
-  if (f->partial) (void)hipFree(f->partial);
+  if (f->partial && f->own_memory) (void)hipFree(f->partial);
   delete f;
 }
 
@@ -350,10 +350,12 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   f->hub_threshold = (int32_t)std::max<int64_t>(1, options().hub_threshold);
   f->hub_segment = (int32_t)std::max<int64_t>(1, options().hub_segment);
   Allocator A{alloc, alloc_ctx, f};
-  void *temp = nullptr;
+  f->alloc = alloc;
+  f->alloc_ctx = alloc_ctx;
+  void *temp = nullptr;  // temporaries: from the callback (kept by the caller) or hipMalloc'd here
   // every exit path below goes through fail() or the success return
   auto fail = [&](int code) {
-    if (temp) (void)hipFree(temp);
+    if (temp && !alloc) (void)hipFree(temp);
     release(f);
     return code;
   };
@@ -398,14 +400,13 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   const size_t bsum_bytes = align_up(bsum_words * 4, 256);
   const size_t rows_bytes = align_up((size_t)scan_len_rows * 4, 256);
   const size_t temp_bytes = bits_bytes + pre_bytes + bsum_bytes + 2 * rows_bytes + 256;
-  {
-    hipError_t e = hipMalloc(&temp, temp_bytes);
-    if (e != hipSuccess) {
-      (void)hipGetLastError();
-      temp = nullptr;
-      return fail(PIPAD_ERR_ALLOC);
-    }
+  if (alloc) {
+    temp = alloc(temp_bytes, alloc_ctx);
+  } else if (hipMalloc(&temp, temp_bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    temp = nullptr;
   }
+  if (!temp) return fail(PIPAD_ERR_ALLOC);
   char *cur = static_cast<char *>(temp);
   uint64_t *bits_all = reinterpret_cast<uint64_t *>(cur); cur += bits_bytes;
   uint32_t *pre = reinterpret_cast<uint32_t *>(cur); cur += pre_bytes;
@@ -495,9 +496,12 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
                      f->rowclass, hubidx, segoff, f->hub_rows, f->hub_item_off, f->item_row,
                      f->item_seg);
   PIPAD_TRY(hipGetLastError());
-  PIPAD_TRY(hipStreamSynchronize(st));  // the temporaries are freed next; inputs may go away
+  if (!alloc) {
+    PIPAD_TRY(hipStreamSynchronize(st));  // the temporaries are freed next
+    (void)hipFree(temp);
+    temp = nullptr;
+  }
 #undef PIPAD_TRY
-  (void)hipFree(temp);
   *out = f;
   return PIPAD_OK;
 }

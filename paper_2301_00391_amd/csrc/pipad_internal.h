@@ -41,6 +41,8 @@ struct pipad_frame {
   int device = 0;
   bool own_memory = true;            // buffers came from hipMalloc (freed in destroy)
   std::vector<void *> owned;         // everything to hipFree when own_memory
+  pipad_alloc_fn alloc = nullptr;    // caller's allocator (also used for the aggregate scratch)
+  void *alloc_ctx = nullptr;
 
   int32_t nnz_c = 0;
   int32_t *rowptr_c = nullptr;       // [n+1]
