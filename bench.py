@@ -41,10 +41,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large")
     ap.add_argument("--epochs", type=int, default=1, help="aggregations per overlap extraction")
-    ap.add_argument("--layout", default="wide", choices=["wide", "list"],
+    ap.add_argument("--layout", default="list", choices=["wide", "list"],
                     help="wide: one [N, k, F] coalescent operand; list: k separate [N, F] matrices")
-    ap.add_argument("--variant", type=int, default=0)
-    ap.add_argument("--rowslots", type=int, default=0)
+    ap.add_argument("--short-max", type=int, default=-1)
+    ap.add_argument("--nt", type=int, default=-1)
     ap.add_argument("--hub-threshold", type=int, default=-1)
     ap.add_argument("--hub-segment", type=int, default=-1)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
@@ -64,8 +64,10 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 3
     pipad.load_library()
-    pipad.set_option("agg_variant", args.variant)
-    pipad.set_option("agg_rowslots", args.rowslots)
+    if args.short_max >= 0:
+        pipad.set_option("short_max", args.short_max)
+    if args.nt >= 0:
+        pipad.set_option("agg_nt", args.nt)
     if args.hub_threshold >= 0:
         pipad.set_option("hub_threshold", args.hub_threshold)
     if args.hub_segment >= 0:

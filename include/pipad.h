@@ -135,15 +135,15 @@ const char *pipad_strerror(int status);
 /* Text of the last HIP runtime error seen by the calling thread ("" if none). */
 const char *pipad_last_hip_error(void);
 
-/* Kernel-selection knobs for measurements; process-wide, not thread-safe.  Unknown keys return
- * PIPAD_ERR_INVALID_ARG.  Keys:
- *   "agg_rowslots" 1 = spare lane groups of a wave take further rows instead of further
- *                  entries of the same row
- *   "agg_variant"  0 = automatic; 1 = one wave covers all k snapshots of a row (coalescent row);
- *                  2 = one snapshot per workgroup column, snapshots spread over workgroups
- *   "hub_threshold"  rows with more than this many (common + longest exclusive) entries are
- *                    split into segments; takes effect for frames built afterwards
- *   "hub_segment"    entries per segment of a split row; takes effect for frames built afterwards
+/* Tuning knobs for measurements; process-wide, not thread-safe.  Unknown keys and negative values
+ * return PIPAD_ERR_INVALID_ARG.  The three length thresholds take effect for frames built
+ * afterwards.  Keys:
+ *   "short_max"      rows with at most this many (common + longest exclusive) entries are walked
+ *                    by one small lane team, several rows per wave (default 32)
+ *   "hub_threshold"  rows with more entries than this are split into segments (default 2048)
+ *   "hub_segment"    entries per segment of a split row (default 1024)
+ *   "agg_nt"         bit 0: non-temporal stores for Y; bit 1: non-temporal loads for the index and
+ *                    scale streams (default 0)
  */
 int pipad_set_option(const char *key, int64_t value);
 int pipad_get_option(const char *key, int64_t *value);

@@ -112,8 +112,8 @@ const char *pipad_last_hip_error(void) { return pipad::g_hip_error.c_str(); }
 static int64_t *option_slot(const char *key) {
   pipad::Options &o = pipad::options();
   if (!key) return nullptr;
-  if (!std::strcmp(key, "agg_variant")) return &o.agg_variant;
-  if (!std::strcmp(key, "agg_rowslots")) return &o.agg_rowslots;
+  if (!std::strcmp(key, "short_max")) return &o.short_max;
+  if (!std::strcmp(key, "agg_nt")) return &o.agg_nt;
   if (!std::strcmp(key, "hub_threshold")) return &o.hub_threshold;
   if (!std::strcmp(key, "hub_segment")) return &o.hub_segment;
   return nullptr;

@@ -36,6 +36,8 @@ struct Parts {  // part 0 = common (from snapshot 0), part 1+t = delta_t
   uint32_t word_off[PIPAD_MAX_K + 2];  // first word of each part in the concatenated prefix array
   int32_t *rowptr_out[PIPAD_MAX_K + 1];
   int32_t *col_out[PIPAD_MAX_K + 1];
+  float *wc[PIPAD_MAX_K];  // column scales of the common entries, one array per snapshot
+  float *wd[PIPAD_MAX_K];  // column scales of the exclusive entries of snapshot t
 };
 
 __host__ __device__ inline int part_snapshot(int part) { return part == 0 ? 0 : part - 1; }
@@ -229,16 +231,19 @@ __global__ __launch_bounds__(kBlock) void k_rowptr(Snaps s, Parts p, const uint3
   p.rowptr_out[part][i] = (int32_t)v;
 }
 
-// ---- per-row metadata: D^-1/2, hub classification ----------------------------------------------
+// ---- per-row metadata: D^-1/2, length classes ---------------------------------------------------
 // dinv_t[i] = (1 + |row i of snapshot t|)^-1/2, evaluated in double and rounded once.
-// hubflag[i] = 1 and nseg[i] = segments when common + longest exclusive length > threshold.
+// Length L(i) = common + longest exclusive row decides the class (see pipad_frame): the three
+// arrays written here are turned into list positions by exclusive prefix sums.
 __global__ __launch_bounds__(kBlock) void k_rowmeta(Snaps s, Parts p, int32_t n, int32_t k,
-                                                     float *dinv, uint8_t *rowclass,
+                                                     float *dinv, uint32_t *shortflag,
                                                      uint32_t *hubflag, uint32_t *nseg,
-                                                     int32_t threshold, int32_t segment) {
+                                                     int32_t short_max, int32_t threshold,
+                                                     int32_t segment) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i > n) return;
-  if (i == n) {  // trailing entries of the two arrays that get scanned
+  if (i == n) {  // trailing entries of the arrays that get scanned
+    shortflag[n] = 0;
     hubflag[n] = 0;
     nseg[n] = 0;
     return;
@@ -252,37 +257,48 @@ __global__ __launch_bounds__(kBlock) void k_rowmeta(Snaps s, Parts p, int32_t n,
   }
   const int64_t total = (int64_t)lc + ldmax;
   const bool hub = total > threshold;
-  rowclass[i] = hub ? 1 : 0;
+  shortflag[i] = total <= short_max ? 1u : 0u;
   hubflag[i] = hub ? 1u : 0u;
   nseg[i] = hub ? (uint32_t)((total + segment - 1) / segment) : 0u;
 }
 
-// Expands the hub rows into (row, segment) work items; hubflag / nseg hold exclusive prefix sums.
-__global__ __launch_bounds__(kBlock) void k_hub_expand(int32_t n, const uint8_t *rowclass,
-                                                        const uint32_t *hubidx,
-                                                        const uint32_t *segoff, int32_t *hub_rows,
-                                                        int32_t *hub_item_off, int32_t *item_row,
-                                                        int32_t *item_seg) {
+// Turns the scanned class arrays into the row lists and the (row, segment) work items.
+// Every row is in exactly one class, so its position in the long list is i - (#short before i)
+// - (#hub before i).
+__global__ __launch_bounds__(kBlock) void k_row_lists(int32_t n, const uint32_t *shortidx,
+                                                       const uint32_t *hubidx,
+                                                       const uint32_t *segoff, int32_t *rows_short,
+                                                       int32_t *rows_long, int32_t *hub_rows,
+                                                       int32_t *hub_item_off, int32_t *item_row,
+                                                       int32_t *item_seg) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i > n) return;
   if (i == n) {
     hub_item_off[hubidx[n]] = (int32_t)segoff[n];
     return;
   }
-  if (!rowclass[i]) return;
-  const uint32_t h = hubidx[i];
-  const uint32_t first = segoff[i], last = segoff[i + 1];
-  hub_rows[h] = (int32_t)i;
-  hub_item_off[h] = (int32_t)first;
-  for (uint32_t q = first; q < last; ++q) {
-    item_row[q] = (int32_t)i;
-    item_seg[q] = (int32_t)(q - first);
+  const uint32_t si = shortidx[i], hi = hubidx[i];
+  if (shortidx[i + 1] != si) {
+    rows_short[si] = (int32_t)i;
+  } else if (hubidx[i + 1] != hi) {
+    const uint32_t first = segoff[i], last = segoff[i + 1];
+    hub_rows[hi] = (int32_t)i;
+    hub_item_off[hi] = (int32_t)first;
+    for (uint32_t q = first; q < last; ++q) {
+      item_row[q] = (int32_t)i;
+      item_seg[q] = (int32_t)(q - first);
+    }
+  } else {
+    rows_long[(uint32_t)i - si - hi] = (int32_t)i;
   }
 }
 
 // ---- scatter ----------------------------------------------------------------------------------
 // grid.y = part; one lane per stored entry of the part's snapshot.
-__global__ __launch_bounds__(kBlock) void k_scatter(Snaps s, Parts p, const uint32_t *pre) {
+// Besides the column index, the column scale dinv_t[column] of the entry is stored: for a common
+// entry once per snapshot, for an exclusive entry for its own snapshot.
+__global__ __launch_bounds__(kBlock) void k_scatter(Snaps s, Parts p, const uint32_t *pre,
+                                                     const float *dinv, int32_t n, int32_t k) {
   const int part = blockIdx.y;
   const int t = part_snapshot(part);
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -292,7 +308,13 @@ __global__ __launch_bounds__(kBlock) void k_scatter(Snaps s, Parts p, const uint
   if (!((sel >> bit) & 1ull)) return;
   const uint32_t off = p.word_off[part];
   const uint32_t dst = pre[off + w] - pre[off] + (uint32_t)__popcll(sel & ((1ull << bit) - 1ull));
-  p.col_out[part][dst] = s.col[t][e];
+  const int32_t c = s.col[t][e];
+  p.col_out[part][dst] = c;
+  if (part == 0) {
+    for (int u = 0; u < k; ++u) p.wc[u][dst] = dinv[(int64_t)u * n + c];
+  } else {
+    p.wd[t][dst] = dinv[(int64_t)t * n + c];
+  }
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -347,7 +369,8 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   f->n = n;
   f->k = k;
   f->own_memory = alloc == nullptr;
-  f->hub_threshold = (int32_t)std::max<int64_t>(1, options().hub_threshold);
+  f->short_max = (int32_t)std::max<int64_t>(0, options().short_max);
+  f->hub_threshold = (int32_t)std::max<int64_t>(f->short_max, options().hub_threshold);
   f->hub_segment = (int32_t)std::max<int64_t>(1, options().hub_segment);
   Allocator A{alloc, alloc_ctx, f};
   f->alloc = alloc;
@@ -374,8 +397,7 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     p.rowptr_out[1 + t] = f->rowptr_d[t];
   }
   f->dinv = static_cast<float *>(A.get((size_t)k * (size_t)std::max(n, 1) * sizeof(float)));
-  f->rowclass = static_cast<uint8_t *>(A.get((size_t)std::max(n, 1)));
-  if (!f->dinv || !f->rowclass) return fail(PIPAD_ERR_ALLOC);
+  if (!f->dinv) return fail(PIPAD_ERR_ALLOC);
 
   // ---- temporaries, one allocation: bitmaps, prefix array, scan block sums, hub scans, flags
   uint32_t nw[PIPAD_MAX_K];
@@ -399,7 +421,7 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   const size_t bsum_words = (std::max<size_t>(m, scan_len_rows) + kScanTile - 1) / kScanTile + 1;
   const size_t bsum_bytes = align_up(bsum_words * 4, 256);
   const size_t rows_bytes = align_up((size_t)scan_len_rows * 4, 256);
-  const size_t temp_bytes = bits_bytes + pre_bytes + bsum_bytes + 2 * rows_bytes + 256;
+  const size_t temp_bytes = bits_bytes + pre_bytes + bsum_bytes + 3 * rows_bytes + 256;
   if (alloc) {
     temp = alloc(temp_bytes, alloc_ctx);
   } else if (hipMalloc(&temp, temp_bytes) != hipSuccess) {
@@ -411,6 +433,7 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   uint64_t *bits_all = reinterpret_cast<uint64_t *>(cur); cur += bits_bytes;
   uint32_t *pre = reinterpret_cast<uint32_t *>(cur); cur += pre_bytes;
   uint32_t *bsum = reinterpret_cast<uint32_t *>(cur); cur += bsum_bytes;
+  uint32_t *shortidx = reinterpret_cast<uint32_t *>(cur); cur += rows_bytes;
   uint32_t *hubidx = reinterpret_cast<uint32_t *>(cur); cur += rows_bytes;
   uint32_t *segoff = reinterpret_cast<uint32_t *>(cur); cur += rows_bytes;
   int *dflags = reinterpret_cast<int *>(cur);  // [0] = validation verdict
@@ -453,21 +476,24 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   hipLaunchKernelGGL(k_rowptr, grid1((int64_t)n + 1, kBlock, k + 1), dim3(kBlock), 0, st, s, p,
                      pre, n);
   hipLaunchKernelGGL(k_rowmeta, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, s, p, n, k,
-                     f->dinv, f->rowclass, hubidx, segoff, f->hub_threshold, f->hub_segment);
+                     f->dinv, shortidx, hubidx, segoff, f->short_max, f->hub_threshold,
+                     f->hub_segment);
   PIPAD_TRY(hipGetLastError());
   {
-    int rc = exclusive_scan(hubidx, scan_len_rows, bsum, st);
+    int rc = exclusive_scan(shortidx, scan_len_rows, bsum, st);
+    if (rc == 0) rc = exclusive_scan(hubidx, scan_len_rows, bsum, st);
     if (rc == 0) rc = exclusive_scan(segoff, scan_len_rows, bsum, st);
     if (rc != 0) return fail(rc);
   }
 
   // ---- the one host synchronisation: sizes of the data-dependent outputs
   uint32_t part_pre[PIPAD_MAX_K + 2];
-  uint32_t hub_totals[2];
+  uint32_t hub_totals[3];
   for (int q = 0; q <= k + 1; ++q)
     PIPAD_TRY(hipMemcpyAsync(&part_pre[q], pre + p.word_off[q], 4, hipMemcpyDeviceToHost, st));
   PIPAD_TRY(hipMemcpyAsync(&hub_totals[0], hubidx + n, 4, hipMemcpyDeviceToHost, st));
   PIPAD_TRY(hipMemcpyAsync(&hub_totals[1], segoff + n, 4, hipMemcpyDeviceToHost, st));
+  PIPAD_TRY(hipMemcpyAsync(&hub_totals[2], shortidx + n, 4, hipMemcpyDeviceToHost, st));
   PIPAD_TRY(hipStreamSynchronize(st));
 
   f->nnz_c = (int32_t)(part_pre[1] - part_pre[0]);
@@ -477,11 +503,20 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   for (int t = 0; t < k; ++t) {
     f->nnz_d[t] = (int32_t)(part_pre[2 + t] - part_pre[1 + t]);
     f->col_d[t] = static_cast<int32_t *>(A.get((size_t)f->nnz_d[t] * 4));
-    if (!f->col_d[t]) return fail(PIPAD_ERR_ALLOC);
+    f->wc[t] = static_cast<float *>(A.get((size_t)f->nnz_c * 4));
+    f->wd[t] = static_cast<float *>(A.get((size_t)f->nnz_d[t] * 4));
+    if (!f->col_d[t] || !f->wc[t] || !f->wd[t]) return fail(PIPAD_ERR_ALLOC);
     p.col_out[1 + t] = f->col_d[t];
+    p.wc[t] = f->wc[t];
+    p.wd[t] = f->wd[t];
   }
   f->n_hub = (int32_t)hub_totals[0];
   f->n_items = (int32_t)hub_totals[1];
+  f->n_short = (int32_t)hub_totals[2];
+  f->n_long = n - f->n_short - f->n_hub;
+  f->rows_short = static_cast<int32_t *>(A.get((size_t)f->n_short * 4));
+  f->rows_long = static_cast<int32_t *>(A.get((size_t)f->n_long * 4));
+  if (!f->rows_short || !f->rows_long) return fail(PIPAD_ERR_ALLOC);
   f->hub_rows = static_cast<int32_t *>(A.get((size_t)f->n_hub * 4));
   f->hub_item_off = static_cast<int32_t *>(A.get(((size_t)f->n_hub + 1) * 4));
   f->item_row = static_cast<int32_t *>(A.get((size_t)f->n_items * 4));
@@ -491,10 +526,11 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   int32_t max_nnz = 0;
   for (int t = 0; t < k; ++t) max_nnz = std::max(max_nnz, s.nnz[t]);
   if (max_nnz > 0)
-    hipLaunchKernelGGL(k_scatter, grid1(max_nnz, kBlock, k + 1), dim3(kBlock), 0, st, s, p, pre);
-  hipLaunchKernelGGL(k_hub_expand, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, n,
-                     f->rowclass, hubidx, segoff, f->hub_rows, f->hub_item_off, f->item_row,
-                     f->item_seg);
+    hipLaunchKernelGGL(k_scatter, grid1(max_nnz, kBlock, k + 1), dim3(kBlock), 0, st, s, p, pre,
+                       f->dinv, n, k);
+  hipLaunchKernelGGL(k_row_lists, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, n, shortidx,
+                     hubidx, segoff, f->rows_short, f->rows_long, f->hub_rows, f->hub_item_off,
+                     f->item_row, f->item_seg);
   PIPAD_TRY(hipGetLastError());
   if (!alloc) {
     PIPAD_TRY(hipStreamSynchronize(st));  // the temporaries are freed next

@@ -26,10 +26,10 @@ int hip_fail(hipError_t e, const char *what);
   } while (0)
 
 struct Options {
-  int64_t agg_variant = 0;     // 0 auto, 1 coalescent row per wave, 2 one snapshot per unit
-  int64_t agg_rowslots = 0;    // 1: idle lane groups of a wave take further rows, not further edges
-  int64_t hub_threshold = 512; // rows longer than this are split into segments
-  int64_t hub_segment = 256;   // entries per segment
+  int64_t short_max = 32;       // rows up to this many entries are walked by one lane team
+  int64_t hub_threshold = 2048; // rows longer than this are split into segments
+  int64_t hub_segment = 1024;   // entries per segment
+  int64_t agg_nt = 0;           // bit 0: non-temporal Y stores, bit 1: non-temporal index streams
 };
 Options &options();
 
@@ -51,11 +51,19 @@ struct pipad_frame {
   int32_t *rowptr_d[PIPAD_MAX_K] = {};  // each [n+1]
   int32_t *col_d[PIPAD_MAX_K] = {};     // each [nnz_d[t]]
   float *dinv = nullptr;             // [k][n]: dinv[t*n + i]
+  // Column scales stored per entry, so that the aggregation streams them instead of gathering
+  // them: wc[t][e] = dinv_t[col_c[e]], wd[t][e] = dinv_t[col_d[t][e]].
+  float *wc[PIPAD_MAX_K] = {};
+  float *wd[PIPAD_MAX_K] = {};
 
-  // Long ("hub") rows: rows whose common + longest exclusive length exceeds hub_threshold are cut
-  // into segments of hub_segment entries; every segment is one work item.
-  int32_t hub_threshold = 0, hub_segment = 0;
-  uint8_t *rowclass = nullptr;       // [n]: 1 = hub row
+  // Rows are binned by length L(i) = common + longest exclusive row:
+  //   short  L <= short_max        one lane team per row, several rows per wave
+  //   long   L <= hub_threshold    one wave per row
+  //   hub    the rest              cut into segments of hub_segment entries, one wave each
+  int32_t short_max = 0, hub_threshold = 0, hub_segment = 0;
+  int32_t n_short = 0, n_long = 0;
+  int32_t *rows_short = nullptr;     // [n_short] ascending row ids
+  int32_t *rows_long = nullptr;      // [n_long]
   int32_t n_hub = 0;
   int32_t *hub_rows = nullptr;       // [n_hub] ascending row ids
   int32_t *hub_item_off = nullptr;   // [n_hub+1] first item of each hub row

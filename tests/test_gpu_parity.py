@@ -12,6 +12,8 @@ from _util import check_overlap, check_y, csr_to_coo, to_gpu_snapshots
 
 pytestmark = pytest.mark.gpu
 
+DEFAULT_OPTIONS = {"short_max": 32, "hub_threshold": 2048, "hub_segment": 1024, "agg_nt": 0}
+
 torch = pytest.importorskip("torch")
 
 
@@ -27,8 +29,7 @@ def pipad():
 @pytest.fixture(autouse=True)
 def _reset_options(pipad):
     yield
-    for key, val in (("agg_variant", 0), ("agg_rowslots", 0), ("hub_threshold", 512),
-                     ("hub_segment", 256)):
+    for key, val in DEFAULT_OPTIONS.items():
         pipad.set_option(key, val)
 
 
@@ -87,10 +88,10 @@ def churned(rng, n, k, p, keep, symmetric=True):
     return out
 
 
-@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("nt", [0, 3])
 @pytest.mark.parametrize("layout", ["list", "wide"])
-def test_tiny_config(pipad, variant, layout):
-    pipad.set_option("agg_variant", variant)
+def test_tiny_config(pipad, nt, layout):
+    pipad.set_option("agg_nt", nt)
     cfg = synth.CONFIGS["tiny"]
     s = synth.make(cfg)
     lists = [(s.rowptr[t], s.col[t]) for t in range(cfg.k)]
@@ -107,22 +108,22 @@ def test_small_config_sliding_frames(pipad, first):
 
 @pytest.mark.parametrize("k,F", [(1, 1), (2, 2), (3, 6), (4, 16), (5, 20), (8, 64), (8, 128),
                                  (2, 130), (16, 32), (3, 260), (32, 4), (8, 256), (7, 12)])
-@pytest.mark.parametrize("variant", [1, 2])
-def test_shapes_and_feature_widths(pipad, k, F, variant):
-    pipad.set_option("agg_variant", variant)
+@pytest.mark.parametrize("short_max", [32, 4])
+def test_shapes_and_feature_widths(pipad, k, F, short_max):
+    pipad.set_option("short_max", short_max)
     rng = np.random.default_rng(1000 * k + F)
     n = 333  # several workgroups and a ragged tail
     lists = churned(rng, n, k, 0.03, 0.8)
     run_case(pipad, n, lists, F, seed=k * 7 + F, layout="wide" if F % 2 == 0 else "list")
 
 
-@pytest.mark.parametrize("variant,rowslots", [(1, 0), (2, 0), (2, 1), (1, 1)])
-def test_hub_rows_are_split_and_rowslots(pipad, variant, rowslots):
-    """Low hub threshold: most rows take the segmented path (partials + fixed-order reduction)."""
-    pipad.set_option("agg_variant", variant)
-    pipad.set_option("agg_rowslots", rowslots)
-    pipad.set_option("hub_threshold", 6)
-    pipad.set_option("hub_segment", 4)
+@pytest.mark.parametrize("short_max,threshold,segment", [(2, 6, 4), (0, 0, 1), (5, 5, 3), (0, 9, 70)])
+def test_row_classes_short_long_hub(pipad, short_max, threshold, segment):
+    """Low thresholds push rows through all three paths; hub rows are cut into segments whose
+    partial sums are added in a fixed order."""
+    pipad.set_option("short_max", short_max)
+    pipad.set_option("hub_threshold", threshold)
+    pipad.set_option("hub_segment", segment)
     rng = np.random.default_rng(77)
     n = 500
     lists = churned(rng, n, 4, 0.04, 0.7)
@@ -170,6 +171,7 @@ def test_library_allocator_and_determinism(pipad):
     n = 400
     lists = churned(rng, n, 4, 0.03, 0.8)
     run_case(pipad, n, lists, 32, seed=9, allocator="library")
+    pipad.set_option("short_max", 3)
     pipad.set_option("hub_threshold", 8)
     pipad.set_option("hub_segment", 8)
     snaps = [(torch.from_numpy(rp).cuda(), torch.from_numpy(c).cuda()) for rp, c in lists]
