@@ -144,6 +144,8 @@ const char *pipad_last_hip_error(void);
  *   "hub_segment"    entries per segment of a split row (default 1024)
  *   "agg_nt"         bit 0: non-temporal stores for Y; bit 1: non-temporal loads for the index and
  *                    scale streams (default 0)
+ *   "agg_parts"      timing aid only (results are incomplete unless 7): bit 0 hub segments,
+ *                    bit 1 long rows, bit 2 short rows take part (default 7)
  */
 int pipad_set_option(const char *key, int64_t value);
 int pipad_get_option(const char *key, int64_t *value);

@@ -52,6 +52,7 @@ struct AggArgs {
   int32_t n_short, n_long, n_items, n_hub;
   int32_t blocks_items, blocks_long;  // workgroups per slice for the first two item kinds
   int32_t nt;         // non-temporal hints (bit 0: Y stores, bit 1: index streams)
+  int32_t parts;      // timing aid: which kinds of work items run (all in normal use)
   int64_t ldx, ldy;
   const int32_t *rowptr_c, *col_c;
   const float *dinv;
@@ -210,7 +211,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const AggArgs a) {
   if (w < a.blocks_items) {
     // ---- one segment of a hub row per wave
     const int64_t item = w * kWavesPerBlock + wave;
-    if (item >= a.n_items) return;
+    if (item >= a.n_items || !(a.parts & 1)) return;
     const int32_t i = a.item_row[item];
     const int32_t v0 = a.item_seg[item] * a.seg, v1 = v0 + a.seg;
     const int32_t cs = a.rowptr_c[i], lc = a.rowptr_c[i + 1] - cs;
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const AggArgs a) {
   if (w < a.blocks_long) {
     // ---- one long row per wave
     const int64_t li = w * kWavesPerBlock + wave;
-    if (li >= a.n_long) return;
+    if (li >= a.n_long || !(a.parts & 2)) return;
     const int32_t i = a.rows_long[li];
     const int32_t cs = a.rowptr_c[i], lc = a.rowptr_c[i + 1] - cs;
     const int32_t ds = s.rpd[i], ld = s.rpd[i + 1] - ds;
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const AggArgs a) {
   w -= a.blocks_long;
   // ---- 64 short rows per wave, one team per row, nteams rows side by side
   const int64_t first = (w * kWavesPerBlock + wave) * kShortRowsPerWave;
-  if (first >= a.n_short) return;
+  if (first >= a.n_short || !(a.parts & 4)) return;
   int32_t r = 0, c0 = 0, c1 = 0, d0 = 0, d1 = 0;
   float di = 0.f;
   if (first + lane < a.n_short) {  // metadata of row `lane` of this wave's 64
@@ -350,6 +351,7 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   a.blocks_items = (f->n_items + kWavesPerBlock - 1) / kWavesPerBlock;
   a.blocks_long = (f->n_long + kWavesPerBlock - 1) / kWavesPerBlock;
   a.nt = (int32_t)options().agg_nt;
+  a.parts = (int32_t)options().agg_parts;
   bool vec4 = F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
   for (int t = 0; t < f->k; ++t) {
     a.rowptr_d[t] = f->rowptr_d[t];

@@ -6,8 +6,8 @@
 //
 //   mark     one lane per stored entry of snapshot 0: find its row, then binary-search its column
 //            in the same row of every other snapshot.  An entry found everywhere is a common
-//            edge: its bit is set in a per-snapshot bitmap (one bit per stored entry) at the
-//            position where each snapshot holds it.
+//            edge: a flag is set for it at the position where each snapshot holds it (a byte
+//            per stored entry, packed into one bit per entry afterwards).
 //   count    popcount per 64-entry word of every output part (common = set bits of snapshot 0's
 //            bitmap, delta_t = clear bits of snapshot t's bitmap) and one exclusive prefix sum
 //            over all words.
@@ -16,7 +16,7 @@
 //            which keeps the ascending column order of the input (stable compaction).
 //
 // All integer work; the outputs are unique, so they are bit-exact regardless of scheduling (the
-// only atomics are integer ORs into the bitmaps).
+// marks are plain byte stores with one writer each; there are no atomics).
 #include <algorithm>
 #include <cstring>
 
@@ -33,6 +33,7 @@ struct Snaps {
 
 struct Parts {  // part 0 = common (from snapshot 0), part 1+t = delta_t
   uint64_t *bits[PIPAD_MAX_K];       // bitmap of snapshot t, ceil(nnz_t/64) words
+  uint8_t *flag8[PIPAD_MAX_K];       // t >= 1: one byte per stored entry, set by k_mark
   uint32_t word_off[PIPAD_MAX_K + 2];  // first word of each part in the concatenated prefix array
   int32_t *rowptr_out[PIPAD_MAX_K + 1];
   int32_t *col_out[PIPAD_MAX_K + 1];
@@ -77,49 +78,102 @@ __global__ __launch_bounds__(kBlock) void k_validate(Snaps s, int32_t n, int32_t
 }
 
 // ---- mark -----------------------------------------------------------------------------------
+// Last row i in [lo, hi] with rowptr[i] <= e, given rowptr[lo] <= e < rowptr[hi + 1].
+__device__ inline int32_t row_of_entry(const int32_t *rp, int32_t lo, int32_t hi, int32_t e) {
+  while (lo < hi) {
+    const int32_t mid = lo + ((hi - lo + 1) >> 1);
+    if (rp[mid] <= e) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+// Position of column c in the ascending run col[a, b), or -1.  The search starts at `guess` and
+// gallops outwards, so it costs one load when the guess is right and O(log distance) otherwise:
+// adjacent snapshots differ in few entries, so the offset of a column within its row barely moves
+// from one snapshot to the next.
+__device__ inline int32_t find_near(const int32_t *col, int32_t a, int32_t b, int32_t guess,
+                                    int32_t c) {
+  if (a >= b) return -1;
+  const int32_t g = min(max(guess, a), b - 1);
+  const int32_t v = col[g];
+  if (v == c) return g;
+  int32_t lo, hi;  // the answer, if any, is the lower bound of c within [lo, hi)
+  if (v < c) {
+    int32_t prev = g, step = 1, cur;
+    while (true) {
+      cur = g + step;
+      if (cur >= b) { cur = b; break; }
+      if (col[cur] >= c) break;
+      prev = cur;
+      step <<= 1;
+    }
+    lo = prev + 1;
+    hi = cur;
+  } else {
+    int32_t next = g, step = 1, cur;
+    while (true) {
+      cur = g - step;
+      if (cur < a) { cur = a - 1; break; }
+      if (col[cur] < c) break;
+      next = cur;
+      step <<= 1;
+    }
+    lo = cur + 1;
+    hi = next;
+  }
+  while (lo < hi) {
+    const int32_t mid = lo + ((hi - lo) >> 1);
+    if (col[mid] < c) lo = mid + 1; else hi = mid;
+  }
+  return (lo < b && col[lo] == c) ? lo : -1;
+}
+
+// One lane per stored entry of snapshot 0.  The rows of a wave's first and last entry are found
+// with wave-uniform searches; every lane then only searches between those two rows.
 __global__ __launch_bounds__(kBlock) void k_mark(Snaps s, Parts p, int32_t n, int32_t k) {
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;  // wave-aligned: 64 | kBlock
+  const int64_t e64 = (int64_t)blockIdx.x * kBlock + threadIdx.x;  // wave-aligned: 64 | kBlock
   const int32_t nnz0 = s.nnz[0];
-  const bool in = e < nnz0;
+  const bool in = e64 < nnz0;
+  const int32_t e = in ? (int32_t)e64 : nnz0 - 1;
+  const int32_t *rp0 = s.rowptr[0];
+  const int32_t e_first = __builtin_amdgcn_readfirstlane((int32_t)min(e64, (int64_t)nnz0 - 1));
+  const int32_t e_last = min(e_first + kWave - 1, nnz0 - 1);
+  const int32_t r_first = row_of_entry(rp0, 0, n - 1, e_first);
+  const int32_t r_last = row_of_entry(rp0, r_first, n - 1, e_last);
+  const int32_t i = row_of_entry(rp0, r_first, r_last, e);
+  const int32_t c = s.col[0][e];
+  int32_t rel = e - rp0[i];  // offset of the entry within its row; the guess for the next snapshot
   bool found = in;
   int32_t pos[PIPAD_MAX_K];
-  if (in) {
-    const int32_t c = s.col[0][e];
-    // row of entry e: the last i with rowptr0[i] <= e (skips empty rows)
-    int32_t lo = 0, hi = n;  // invariant: rowptr0[lo] <= e < rowptr0[hi]
-    const int32_t *rp0 = s.rowptr[0];
-    while (hi - lo > 1) {
-      const int32_t mid = lo + ((hi - lo) >> 1);
-      if (rp0[mid] <= (int32_t)e) lo = mid; else hi = mid;
-    }
-    const int32_t i = lo;
 #pragma unroll
-    for (int t = 1; t < PIPAD_MAX_K; ++t) {
-      pos[t] = 0;
-      if (t < k && found) {
-        const int32_t *col = s.col[t];
-        int32_t a = s.rowptr[t][i];
-        const int32_t b = s.rowptr[t][i + 1];
-        int32_t len = b - a;
-        while (len > 0) {  // lower_bound(c)
-          const int32_t half = len >> 1;
-          if (col[a + half] < c) { a += half + 1; len -= half + 1; } else { len = half; }
-        }
-        if (a < b && col[a] == c) pos[t] = a; else found = false;
-      }
+  for (int t = 1; t < PIPAD_MAX_K; ++t) {
+    pos[t] = 0;
+    if (t < k && found) {
+      const int32_t a = s.rowptr[t][i];
+      const int32_t b = s.rowptr[t][i + 1];
+      const int32_t at = find_near(s.col[t], a, b, a + rel, c);
+      if (at >= 0) { pos[t] = at; rel = at - a; } else { found = false; }
     }
   }
   const uint64_t word = __ballot(found);
-  if (threadIdx.x % kWave == 0 && e < nnz0) p.bits[0][e >> 6] = word;
+  if (threadIdx.x % kWave == 0 && in) p.bits[0][e64 >> 6] = word;
   if (found) {
+    // plain byte stores (every byte has one writer); positions ascend with the lane, so the
+    // stores of a wave fall into a few cache lines
 #pragma unroll
-    for (int t = 1; t < PIPAD_MAX_K; ++t) {
-      if (t < k) {
-        uint32_t *w32 = reinterpret_cast<uint32_t *>(p.bits[t]);
-        atomicOr(&w32[pos[t] >> 5], 1u << (pos[t] & 31));
-      }
-    }
+    for (int t = 1; t < PIPAD_MAX_K; ++t)
+      if (t < k) p.flag8[t][pos[t]] = 1;
   }
+}
+
+// Packs the byte flags of snapshots 1 .. k-1 into bitmaps (grid.y = t - 1), 64 entries per wave.
+__global__ __launch_bounds__(kBlock) void k_pack(Snaps s, Parts p) {
+  const int t = blockIdx.y + 1;
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int32_t nnz = s.nnz[t];
+  const bool set = e < nnz && p.flag8[t][e] != 0;
+  const uint64_t word = __ballot(set);
+  if (threadIdx.x % kWave == 0 && e < nnz) p.bits[t][e >> 6] = word;
 }
 
 // ---- count ----------------------------------------------------------------------------------
@@ -236,7 +290,8 @@ __global__ __launch_bounds__(kBlock) void k_rowptr(Snaps s, Parts p, const uint3
 // Length L(i) = common + longest exclusive row decides the class (see pipad_frame): the three
 // arrays written here are turned into list positions by exclusive prefix sums.
 __global__ __launch_bounds__(kBlock) void k_rowmeta(Snaps s, Parts p, int32_t n, int32_t k,
-                                                     float *dinv, uint32_t *shortflag,
+                                                     float *dinv, float *dinv_nk,
+                                                     uint32_t *shortflag,
                                                      uint32_t *hubflag, uint32_t *nseg,
                                                      int32_t short_max, int32_t threshold,
                                                      int32_t segment) {
@@ -252,7 +307,9 @@ __global__ __launch_bounds__(kBlock) void k_rowmeta(Snaps s, Parts p, int32_t n,
   int32_t ldmax = 0;
   for (int t = 0; t < k; ++t) {
     const int32_t len = s.rowptr[t][i + 1] - s.rowptr[t][i];
-    dinv[(int64_t)t * n + i] = (float)(1.0 / sqrt((double)(len + 1)));
+    const float v = (float)(1.0 / sqrt((double)(len + 1)));
+    dinv[(int64_t)t * n + i] = v;
+    dinv_nk[i * k + t] = v;  // node-major copy for the scatter step (one line per node)
     ldmax = max(ldmax, len - lc);
   }
   const int64_t total = (int64_t)lc + ldmax;
@@ -296,9 +353,9 @@ __global__ __launch_bounds__(kBlock) void k_row_lists(int32_t n, const uint32_t 
 // ---- scatter ----------------------------------------------------------------------------------
 // grid.y = part; one lane per stored entry of the part's snapshot.
 // Besides the column index, the column scale dinv_t[column] of the entry is stored: for a common
-// entry once per snapshot, for an exclusive entry for its own snapshot.
+// entry once per snapshot, for an exclusive entry for its own snapshot.  dinv_nk is [n][k].
 __global__ __launch_bounds__(kBlock) void k_scatter(Snaps s, Parts p, const uint32_t *pre,
-                                                     const float *dinv, int32_t n, int32_t k) {
+                                                     const float *dinv_nk, int32_t n, int32_t k) {
   const int part = blockIdx.y;
   const int t = part_snapshot(part);
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -311,13 +368,43 @@ __global__ __launch_bounds__(kBlock) void k_scatter(Snaps s, Parts p, const uint
   const int32_t c = s.col[t][e];
   p.col_out[part][dst] = c;
   if (part == 0) {
-    for (int u = 0; u < k; ++u) p.wc[u][dst] = dinv[(int64_t)u * n + c];
+    for (int u = 0; u < k; ++u) p.wc[u][dst] = dinv_nk[(int64_t)c * k + u];
   } else {
-    p.wd[t][dst] = dinv[(int64_t)t * n + c];
+    p.wd[t][dst] = dinv_nk[(int64_t)c * k + t];
+  }
+}
+
+// Collects the data-dependent sizes into one small buffer for a single copy to the host:
+// out[0 .. k+1] = prefix at the start of every part (and the end of the last), then the numbers
+// of hub rows, hub segments and short rows.
+__global__ void k_totals(Parts p, const uint32_t *pre, int32_t k, int32_t n,
+                         const uint32_t *hubidx, const uint32_t *segoff,
+                         const uint32_t *shortidx, uint32_t *out) {
+  const int q = threadIdx.x;
+  if (q <= k + 1) out[q] = pre[p.word_off[q]];
+  if (q == 0) {
+    out[k + 2] = hubidx[n];
+    out[k + 3] = segoff[n];
+    out[k + 4] = shortidx[n];
   }
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Sub-allocates many arrays from one allocation: first every array registers its size, then
+// assign() hands out 256-byte aligned pieces of the block.
+struct Arena {
+  struct Want { void **slot; size_t offset; };
+  std::vector<Want> wants;
+  size_t total = 0;
+  template <class T> void want(T **slot, size_t count) {
+    wants.push_back({reinterpret_cast<void **>(slot), total});
+    total += align_up(std::max<size_t>(count * sizeof(T), 1), 256);
+  }
+  void assign(void *base) {
+    for (const Want &w : wants) *w.slot = static_cast<char *>(base) + w.offset;
+  }
+};
 
 struct Allocator {
   pipad_alloc_fn fn;
@@ -358,7 +445,6 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
                   pipad_alloc_fn alloc, void *alloc_ctx, hipStream_t st, pipad_frame **out) {
   Snaps s;
   std::memset(&s, 0, sizeof(s));
-  int64_t total_words = 0;
   for (int t = 0; t < k; ++t) {
     s.rowptr[t] = snaps[t].rowptr;
     s.col[t] = snaps[t].colidx;
@@ -384,26 +470,13 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   };
   if (hipGetDevice(&f->device) != hipSuccess) return fail(hip_fail(hipGetLastError(), "hipGetDevice"));
 
-  // ---- persistent buffers whose size is known up front
+  // ---- sizes known up front: row pointers and D^-1/2 (persistent), all temporaries
   Parts p;
   std::memset(&p, 0, sizeof(p));
-  const size_t rp_bytes = ((size_t)n + 1) * sizeof(int32_t);
-  f->rowptr_c = static_cast<int32_t *>(A.get(rp_bytes));
-  if (!f->rowptr_c) return fail(PIPAD_ERR_ALLOC);
-  p.rowptr_out[0] = f->rowptr_c;
-  for (int t = 0; t < k; ++t) {
-    f->rowptr_d[t] = static_cast<int32_t *>(A.get(rp_bytes));
-    if (!f->rowptr_d[t]) return fail(PIPAD_ERR_ALLOC);
-    p.rowptr_out[1 + t] = f->rowptr_d[t];
-  }
-  f->dinv = static_cast<float *>(A.get((size_t)k * (size_t)std::max(n, 1) * sizeof(float)));
-  if (!f->dinv) return fail(PIPAD_ERR_ALLOC);
-
-  // ---- temporaries, one allocation: bitmaps, prefix array, scan block sums, hub scans, flags
   uint32_t nw[PIPAD_MAX_K];
   for (int t = 0; t < k; ++t) {
     nw[t] = (uint32_t)(((int64_t)s.nnz[t] + 63) / 64);
-    total_words += nw[t];
+
   }
   // parts: common uses snapshot 0's words, delta_t uses snapshot t's words
   int64_t m64 = nw[0];
@@ -414,33 +487,48 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   p.word_off[0] = 0;
   p.word_off[1] = nw[0];
   for (int t = 0; t < k; ++t) p.word_off[2 + t] = p.word_off[1 + t] + nw[t];
-
-  const size_t bits_bytes = align_up((size_t)total_words * 8, 256);
-  const size_t pre_bytes = align_up((size_t)m * 4, 256);
   const uint32_t scan_len_rows = (uint32_t)n + 1;
-  const size_t bsum_words = (std::max<size_t>(m, scan_len_rows) + kScanTile - 1) / kScanTile + 1;
-  const size_t bsum_bytes = align_up(bsum_words * 4, 256);
-  const size_t rows_bytes = align_up((size_t)scan_len_rows * 4, 256);
-  const size_t temp_bytes = bits_bytes + pre_bytes + bsum_bytes + 3 * rows_bytes + 256;
+
+  Arena keep1;
+  keep1.want(&f->rowptr_c, (size_t)n + 1);
+  for (int t = 0; t < k; ++t) keep1.want(&f->rowptr_d[t], (size_t)n + 1);
+  keep1.want(&f->dinv, (size_t)k * n);
+  {
+    void *base = A.get(keep1.total);
+    if (!base) return fail(PIPAD_ERR_ALLOC);
+    keep1.assign(base);
+  }
+  p.rowptr_out[0] = f->rowptr_c;
+  for (int t = 0; t < k; ++t) p.rowptr_out[1 + t] = f->rowptr_d[t];
+
+  Arena tmp;
+  size_t flag_bytes = 0;  // byte flags of snapshots 1 .. k-1 come first and are cleared together
+  for (int t = 1; t < k; ++t) {
+    tmp.want(&p.flag8[t], (size_t)s.nnz[t]);
+    flag_bytes = tmp.total;
+  }
+  for (int t = 0; t < k; ++t) tmp.want(&p.bits[t], (size_t)nw[t]);
+  uint32_t *pre = nullptr, *bsum = nullptr, *shortidx = nullptr, *hubidx = nullptr,
+           *segoff = nullptr, *totals = nullptr;
+  float *dinv_nk = nullptr;
+  int *dflags = nullptr;
+  tmp.want(&pre, (size_t)m);
+  tmp.want(&bsum, (std::max<size_t>(m, scan_len_rows) + kScanTile - 1) / kScanTile + 1);
+  tmp.want(&shortidx, (size_t)scan_len_rows);
+  tmp.want(&hubidx, (size_t)scan_len_rows);
+  tmp.want(&segoff, (size_t)scan_len_rows);
+  tmp.want(&dinv_nk, (size_t)k * n);
+  tmp.want(&totals, (size_t)PIPAD_MAX_K + 8);
+  tmp.want(&dflags, (size_t)64);
   if (alloc) {
-    temp = alloc(temp_bytes, alloc_ctx);
-  } else if (hipMalloc(&temp, temp_bytes) != hipSuccess) {
+    temp = alloc(tmp.total, alloc_ctx);
+  } else if (hipMalloc(&temp, tmp.total) != hipSuccess) {
     (void)hipGetLastError();
     temp = nullptr;
   }
   if (!temp) return fail(PIPAD_ERR_ALLOC);
-  char *cur = static_cast<char *>(temp);
-  uint64_t *bits_all = reinterpret_cast<uint64_t *>(cur); cur += bits_bytes;
-  uint32_t *pre = reinterpret_cast<uint32_t *>(cur); cur += pre_bytes;
-  uint32_t *bsum = reinterpret_cast<uint32_t *>(cur); cur += bsum_bytes;
-  uint32_t *shortidx = reinterpret_cast<uint32_t *>(cur); cur += rows_bytes;
-  uint32_t *hubidx = reinterpret_cast<uint32_t *>(cur); cur += rows_bytes;
-  uint32_t *segoff = reinterpret_cast<uint32_t *>(cur); cur += rows_bytes;
-  int *dflags = reinterpret_cast<int *>(cur);  // [0] = validation verdict
-  {
-    uint64_t *b = bits_all;
-    for (int t = 0; t < k; ++t) { p.bits[t] = b; b += nw[t]; }
-  }
+  tmp.assign(temp);
+
   auto hipcheck = [&](hipError_t e, const char *what) { return e == hipSuccess ? 0 : hip_fail(e, what); };
 #define PIPAD_TRY(call)                                   \
   do {                                                    \
@@ -448,7 +536,7 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     if (rc__ != 0) return fail(rc__);                     \
   } while (0)
 
-  PIPAD_TRY(hipMemsetAsync(temp, 0, bits_bytes, st));
+  if (flag_bytes) PIPAD_TRY(hipMemsetAsync(temp, 0, flag_bytes, st));
   PIPAD_TRY(hipMemsetAsync(dflags, 0, 256, st));
   PIPAD_TRY(hipMemsetAsync(pre + (m - 1), 0, 4, st));  // trailing word
 
@@ -464,6 +552,12 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
 
   if (s.nnz[0] > 0)
     hipLaunchKernelGGL(k_mark, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, n, k);
+  {
+    int32_t max_later = 0;
+    for (int t = 1; t < k; ++t) max_later = std::max(max_later, s.nnz[t]);
+    if (max_later > 0)
+      hipLaunchKernelGGL(k_pack, grid1(max_later, kBlock, k - 1), dim3(kBlock), 0, st, s, p);
+  }
   uint32_t max_nw = 0;
   for (int t = 0; t < k; ++t) max_nw = std::max(max_nw, nw[t]);
   if (max_nw > 0)
@@ -476,7 +570,7 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   hipLaunchKernelGGL(k_rowptr, grid1((int64_t)n + 1, kBlock, k + 1), dim3(kBlock), 0, st, s, p,
                      pre, n);
   hipLaunchKernelGGL(k_rowmeta, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, s, p, n, k,
-                     f->dinv, shortidx, hubidx, segoff, f->short_max, f->hub_threshold,
+                     f->dinv, dinv_nk, shortidx, hubidx, segoff, f->short_max, f->hub_threshold,
                      f->hub_segment);
   PIPAD_TRY(hipGetLastError());
   {
@@ -487,47 +581,51 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   }
 
   // ---- the one host synchronisation: sizes of the data-dependent outputs
-  uint32_t part_pre[PIPAD_MAX_K + 2];
-  uint32_t hub_totals[3];
-  for (int q = 0; q <= k + 1; ++q)
-    PIPAD_TRY(hipMemcpyAsync(&part_pre[q], pre + p.word_off[q], 4, hipMemcpyDeviceToHost, st));
-  PIPAD_TRY(hipMemcpyAsync(&hub_totals[0], hubidx + n, 4, hipMemcpyDeviceToHost, st));
-  PIPAD_TRY(hipMemcpyAsync(&hub_totals[1], segoff + n, 4, hipMemcpyDeviceToHost, st));
-  PIPAD_TRY(hipMemcpyAsync(&hub_totals[2], shortidx + n, 4, hipMemcpyDeviceToHost, st));
+  uint32_t host_totals[PIPAD_MAX_K + 8];
+  hipLaunchKernelGGL(k_totals, dim3(1), dim3(kWave), 0, st, p, pre, k, n, hubidx, segoff, shortidx,
+                     totals);
+  PIPAD_TRY(hipGetLastError());
+  PIPAD_TRY(hipMemcpyAsync(host_totals, totals, sizeof(uint32_t) * (size_t)(k + 5),
+                           hipMemcpyDeviceToHost, st));
   PIPAD_TRY(hipStreamSynchronize(st));
 
-  f->nnz_c = (int32_t)(part_pre[1] - part_pre[0]);
-  f->col_c = static_cast<int32_t *>(A.get((size_t)f->nnz_c * 4));
-  if (!f->col_c) return fail(PIPAD_ERR_ALLOC);
+  f->nnz_c = (int32_t)(host_totals[1] - host_totals[0]);
+  for (int t = 0; t < k; ++t) f->nnz_d[t] = (int32_t)(host_totals[2 + t] - host_totals[1 + t]);
+  f->n_hub = (int32_t)host_totals[k + 2];
+  f->n_items = (int32_t)host_totals[k + 3];
+  f->n_short = (int32_t)host_totals[k + 4];
+  f->n_long = n - f->n_short - f->n_hub;
+
+  Arena keep2;
+  keep2.want(&f->col_c, (size_t)f->nnz_c);
+  for (int t = 0; t < k; ++t) {
+    keep2.want(&f->col_d[t], (size_t)f->nnz_d[t]);
+    keep2.want(&f->wc[t], (size_t)f->nnz_c);
+    keep2.want(&f->wd[t], (size_t)f->nnz_d[t]);
+  }
+  keep2.want(&f->rows_short, (size_t)f->n_short);
+  keep2.want(&f->rows_long, (size_t)f->n_long);
+  keep2.want(&f->hub_rows, (size_t)f->n_hub);
+  keep2.want(&f->hub_item_off, (size_t)f->n_hub + 1);
+  keep2.want(&f->item_row, (size_t)f->n_items);
+  keep2.want(&f->item_seg, (size_t)f->n_items);
+  {
+    void *base = A.get(keep2.total);
+    if (!base) return fail(PIPAD_ERR_ALLOC);
+    keep2.assign(base);
+  }
   p.col_out[0] = f->col_c;
   for (int t = 0; t < k; ++t) {
-    f->nnz_d[t] = (int32_t)(part_pre[2 + t] - part_pre[1 + t]);
-    f->col_d[t] = static_cast<int32_t *>(A.get((size_t)f->nnz_d[t] * 4));
-    f->wc[t] = static_cast<float *>(A.get((size_t)f->nnz_c * 4));
-    f->wd[t] = static_cast<float *>(A.get((size_t)f->nnz_d[t] * 4));
-    if (!f->col_d[t] || !f->wc[t] || !f->wd[t]) return fail(PIPAD_ERR_ALLOC);
     p.col_out[1 + t] = f->col_d[t];
     p.wc[t] = f->wc[t];
     p.wd[t] = f->wd[t];
   }
-  f->n_hub = (int32_t)hub_totals[0];
-  f->n_items = (int32_t)hub_totals[1];
-  f->n_short = (int32_t)hub_totals[2];
-  f->n_long = n - f->n_short - f->n_hub;
-  f->rows_short = static_cast<int32_t *>(A.get((size_t)f->n_short * 4));
-  f->rows_long = static_cast<int32_t *>(A.get((size_t)f->n_long * 4));
-  if (!f->rows_short || !f->rows_long) return fail(PIPAD_ERR_ALLOC);
-  f->hub_rows = static_cast<int32_t *>(A.get((size_t)f->n_hub * 4));
-  f->hub_item_off = static_cast<int32_t *>(A.get(((size_t)f->n_hub + 1) * 4));
-  f->item_row = static_cast<int32_t *>(A.get((size_t)f->n_items * 4));
-  f->item_seg = static_cast<int32_t *>(A.get((size_t)f->n_items * 4));
-  if (!f->hub_rows || !f->hub_item_off || !f->item_row || !f->item_seg) return fail(PIPAD_ERR_ALLOC);
 
   int32_t max_nnz = 0;
   for (int t = 0; t < k; ++t) max_nnz = std::max(max_nnz, s.nnz[t]);
   if (max_nnz > 0)
     hipLaunchKernelGGL(k_scatter, grid1(max_nnz, kBlock, k + 1), dim3(kBlock), 0, st, s, p, pre,
-                       f->dinv, n, k);
+                       dinv_nk, n, k);
   hipLaunchKernelGGL(k_row_lists, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, n, shortidx,
                      hubidx, segoff, f->rows_short, f->rows_long, f->hub_rows, f->hub_item_off,
                      f->item_row, f->item_seg);
