@@ -42,6 +42,7 @@ namespace pipad {
 namespace {
 
 constexpr int kShortRowsPerWave = 64;
+constexpr int kLongRowsPerWave = 8;
 
 struct AggArgs {
   int32_t n, k, F;
@@ -106,6 +107,7 @@ template <> struct V<1> {
 
 // What a lane needs to know about its slice.
 struct Slice {
+  const float *xt;          // X_t (the same for the whole workgroup)
   const float *xb;          // X_t + feature column of this lane
   float *yb;                // Y_t + feature column of this lane
   const float *dv;          // dinv_t
@@ -122,6 +124,7 @@ __device__ inline Slice slice_setup(const AggArgs &a, int slice, int fl, int vec
   s.fcol = (fc << a.ls_log2) * vec + fl * vec;
   s.fvalid = s.fcol < a.F;
   const int col = s.fvalid ? s.fcol : 0;  // idle lanes read column 0 and never store
+  s.xt = a.X[t];
   s.xb = a.X[t] + col;
   s.yb = a.Y[t] + col;
   s.dv = a.dinv + (int64_t)t * a.n;
@@ -132,57 +135,98 @@ __device__ inline Slice slice_setup(const AggArgs &a, int slice, int fl, int vec
   return s;
 }
 
+// One entry as fetched (column index and column scale) ...
+struct Raw {
+  int32_t c;
+  float w;
+};
+// ... and as staged in LDS for the lane groups: where its feature row starts, and the scale.
+struct Staged {
+  uint32_t off;  // FAST: byte offset of row c within the slice's matrix; else c itself
+  float w;
+};
+
+// Entry base + q of a list, or (own row, weight 0) past its end: such a filler may be gathered
+// harmlessly, which lets the FAST inner loop run without bounds checks.
+__device__ inline Raw fetch_entry(const int32_t *__restrict__ col, const float *__restrict__ w,
+                                  int32_t start, int32_t len, int32_t pos, int32_t self, bool nt) {
+  Raw r;
+  r.c = self;
+  r.w = 0.f;
+  if (pos < len) {
+    if (nt) {
+      r.c = __builtin_nontemporal_load(col + start + pos);
+      r.w = __builtin_nontemporal_load(w + start + pos);
+    } else {
+      r.c = col[start + pos];
+      r.w = w[start + pos];
+    }
+  }
+  return r;
+}
+
 // Adds sum_e w[e] * X[col[e], :] over the `len` entries starting at `start` to acc.
+//   first      entry q of the list, already fetched by the caller (fetch_entry(..., q, ...))
 //   team_base  first lane of the team; team_lanes lanes fetch a chunk of entries together
 //   q          this lane's index within the team
 //   slot/nslots  the team's lane groups take entries slot, slot + nslots, ... of each chunk
-// Every lane of a team runs the same number of iterations (entries past the end are given weight
-// zero and the row's own index), so ds_bpermute never reads from a lane that has left the loop.
-template <int VEC, int UNR>
+//   lds        this wave's 64 staging slots
+// A chunk is fetched with one coalesced load of indices and scales (the next chunk is requested
+// before the current chunk's gathers), turned into row offsets once per entry, and parked in LDS;
+// every lane group then picks its entry up with a single 8-byte LDS read, so the inner loop is
+// one LDS read, one add, one 16-byte gather and VEC fused multiply-adds per entry.
+// The FAST inner loop needs nslots * UNR to divide team_lanes.
+template <int VEC, int UNR, bool FAST>
 __device__ inline void walk(const int32_t *__restrict__ col, const float *__restrict__ w,
-                            int32_t start, int32_t len, int team_base, int team_lanes, int q,
-                            int slot, int nslots, const float *xb, int64_t ldx, int32_t self,
-                            bool nt, typename V<VEC>::T &acc) {
+                            int32_t start, int32_t len, Raw first, int team_base, int team_lanes,
+                            int q, int slot, int nslots, const Slice &s, int64_t ldx, int32_t self,
+                            bool nt, Staged *lds, typename V<VEC>::T &acc) {
   using VT = V<VEC>;
+  if (len <= 0) return;
+  const uint32_t row_bytes = (uint32_t)ldx * 4u;
+  // FAST addressing: wave-uniform matrix base + 32-bit (row offset + this lane's column offset)
+  const char *xbytes = reinterpret_cast<const char *>(s.xt);
+  const uint32_t lane_bytes = (uint32_t)(s.fvalid ? s.fcol : 0) * 4u;
+  const float *xcol = s.xb;
+  Raw mine = first, next = first;
   for (int32_t base = 0; base < len; base += team_lanes) {
     const int32_t cnt = min(team_lanes, len - base);
-    int32_t myc = self;
-    float myw = 0.f;
-    if (q < cnt) {
-      if (nt) {
-        myc = __builtin_nontemporal_load(col + start + base + q);
-        myw = __builtin_nontemporal_load(w + start + base + q);
-      } else {
-        myc = col[start + base + q];
-        myw = w[start + base + q];
-      }
-    }
+    if (base + team_lanes < len) next = fetch_entry(col, w, start, len, base + team_lanes + q, self, nt);
+    Staged st;
+    st.off = FAST ? (uint32_t)mine.c * row_bytes : (uint32_t)mine.c;
+    st.w = mine.w;
+    lds[team_base + q] = st;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     for (int32_t e0 = 0; e0 < cnt; e0 += nslots * UNR) {
-      int32_t j[UNR];
-      float wt[UNR];
+      Staged en[UNR];
       typename VT::T x[UNR];
 #pragma unroll
       for (int u = 0; u < UNR; ++u) {
-        const int32_t e = e0 + u * nslots + slot;
-        const int src = team_base + (e < cnt ? e : 0);
-        j[u] = __shfl(myc, src, kWave);
-        wt[u] = __shfl(myw, src, kWave);
-        if (e >= cnt) { j[u] = self; wt[u] = 0.f; }
+        int32_t e = e0 + u * nslots + slot;
+        if (!FAST) e = min(e, team_lanes - 1);
+        en[u] = lds[team_base + e];
+        if (!FAST && e0 + u * nslots + slot >= cnt) en[u].w = 0.f;
       }
 #pragma unroll
-      for (int u = 0; u < UNR; ++u) x[u] = VT::load(xb + (int64_t)j[u] * ldx);
+      for (int u = 0; u < UNR; ++u) {
+        if (FAST)
+          x[u] = VT::load(reinterpret_cast<const float *>(xbytes + (en[u].off + lane_bytes)));
+        else
+          x[u] = VT::load(xcol + (int64_t)en[u].off * ldx);
+      }
 #pragma unroll
-      for (int u = 0; u < UNR; ++u) VT::fma(acc, wt[u], x[u]);
+      for (int u = 0; u < UNR; ++u) VT::fma(acc, en[u].w, x[u]);
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    mine = next;
   }
 }
 
 // Self-loop term, row scale, store.
 template <int VEC>
 __device__ inline void finish_row(const AggArgs &a, const Slice &s, int32_t i, float di,
-                                  typename V<VEC>::T acc) {
+                                  typename V<VEC>::T xi, typename V<VEC>::T acc) {
   using VT = V<VEC>;
-  typename VT::T xi = VT::load(s.xb + (int64_t)i * a.ldx);
   VT::fma(acc, di, xi);
   VT::store(s.yb + (int64_t)i * a.ldy, VT::scale(di, acc), a.nt & 1);
 }
@@ -192,9 +236,15 @@ __device__ inline void reduce_slots(int ls_log2, typename V<VEC>::T &acc) {
   for (int m = kWave >> 1; m >= (1 << ls_log2); m >>= 1) V<VEC>::add(acc, V<VEC>::shfl_xor(acc, m));
 }
 
-template <int VEC>
+template <int VEC, bool FAST>
 __global__ __launch_bounds__(kBlock) void k_aggregate(const AggArgs a) {
   using VT = V<VEC>;
+  // Row gathers in flight per lane.  Measured on MI355X (N = 1M R-MAT frame): 4 beats 2 and 8 on
+  // both paths; deeper bursts only queue up in front of the L1's miss slots.
+  constexpr int UL = FAST ? 4 : 1;  // wave-wide teams (long rows, hub segments)
+  constexpr int US = FAST ? 4 : 1;  // row-wide teams (short rows)
+  __shared__ Staged staging[kWavesPerBlock][kWave];
+  Staged *lds = staging[threadIdx.x / kWave];
   const int lane = threadIdx.x % kWave;
   const int wave = threadIdx.x / kWave;
   const int ls = 1 << a.ls_log2;
@@ -219,57 +269,85 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const AggArgs a) {
     typename VT::T acc = VT::zero();
     // positions [v0, v1) of the virtual list "common entries, then exclusive entries"
     const int32_t c0 = min(v0, lc), c1 = min(v1, lc);
-    walk<VEC, 8>(a.col_c, s.wc, cs + c0, c1 - c0, 0, kWave, lane, team, nteams, s.xb, a.ldx, i, ntl, acc);
     const int32_t d0 = min(max(v0 - lc, 0), ld), d1 = min(max(v1 - lc, 0), ld);
-    walk<VEC, 8>(s.cd, s.wd, ds + d0, d1 - d0, 0, kWave, lane, team, nteams, s.xb, a.ldx, i, ntl, acc);
+    const Raw fc = fetch_entry(a.col_c, s.wc, cs + c0, c1 - c0, lane, i, ntl);
+    const Raw fd = fetch_entry(s.cd, s.wd, ds + d0, d1 - d0, lane, i, ntl);
+    walk<VEC, UL, FAST>(a.col_c, s.wc, cs + c0, c1 - c0, fc, 0, kWave, lane, team, nteams, s, a.ldx, i, ntl, lds, acc);
+    walk<VEC, UL, FAST>(s.cd, s.wd, ds + d0, d1 - d0, fd, 0, kWave, lane, team, nteams, s, a.ldx, i, ntl, lds, acc);
     reduce_slots<VEC>(a.ls_log2, acc);
     if (team == 0 && s.fvalid)
       VT::store(a.partial + (((int64_t)item * a.nslices + slice) << a.ls_log2) * VEC + fl * VEC, acc, false);
     return;
   }
   w -= a.blocks_items;
-  if (w < a.blocks_long) {
-    // ---- one long row per wave
-    const int64_t li = w * kWavesPerBlock + wave;
-    if (li >= a.n_long || !(a.parts & 2)) return;
-    const int32_t i = a.rows_long[li];
-    const int32_t cs = a.rowptr_c[i], lc = a.rowptr_c[i + 1] - cs;
-    const int32_t ds = s.rpd[i], ld = s.rpd[i + 1] - ds;
+
+  // ---- rows: a wave takes a batch of consecutive rows of one list.  Long rows: the whole wave
+  //      works on one row at a time (its lane groups take different entries).  Short rows: one
+  //      lane group per row, nteams rows at a time.  The metadata of the whole batch is loaded
+  //      up front (lane l holds row l of the batch), and while one row is being gathered the
+  //      first chunk of entries and the self-loop row of the next one are already on their way.
+  const bool long_rows = w < a.blocks_long;
+  if (!long_rows) w -= a.blocks_long;
+  const int32_t *list = long_rows ? a.rows_long : a.rows_short;
+  const int64_t list_len = long_rows ? a.n_long : a.n_short;
+  const int batch = long_rows ? kLongRowsPerWave : kShortRowsPerWave;
+  const int64_t first = (w * kWavesPerBlock + wave) * batch;
+  if (first >= list_len || !(a.parts & (long_rows ? 2 : 4))) return;
+  const int rows_here = (int)min((int64_t)batch, list_len - first);
+  int32_t r = 0, mc0 = 0, mc1 = 0, md0 = 0, md1 = 0;
+  float mdi = 0.f;
+  if (lane < rows_here) {
+    r = list[first + lane];
+    mc0 = a.rowptr_c[r]; mc1 = a.rowptr_c[r + 1];
+    md0 = s.rpd[r]; md1 = s.rpd[r + 1];
+    mdi = s.dv[r];
+  }
+  const int per_step = long_rows ? 1 : nteams;          // rows worked on side by side
+  const int team_base = long_rows ? 0 : team << a.ls_log2;
+  const int team_lanes = long_rows ? kWave : ls;
+  const int q = long_rows ? lane : fl;
+  const int slot = long_rows ? team : 0;
+  const int nslots = long_rows ? nteams : 1;
+
+  struct Item {
+    int32_t i, cs, clen, ds, dlen;
+    float di;
+    bool have;
+    Raw fc, fd;
+    typename VT::T xi;
+  };
+  auto prefetch = [&](int step) {
+    Item it;
+    const int li = step * per_step + (long_rows ? 0 : team);
+    it.have = li < rows_here;
+    const int src = it.have ? li : 0;
+    it.i = __shfl(r, src, kWave);
+    it.cs = __shfl(mc0, src, kWave);
+    it.clen = __shfl(mc1, src, kWave) - it.cs;
+    it.ds = __shfl(md0, src, kWave);
+    it.dlen = __shfl(md1, src, kWave) - it.ds;
+    it.di = __shfl(mdi, src, kWave);
+    if (!it.have) { it.clen = 0; it.dlen = 0; }
+    it.fc = fetch_entry(a.col_c, s.wc, it.cs, it.clen, q, it.i, ntl);
+    it.fd = fetch_entry(s.cd, s.wd, it.ds, it.dlen, q, it.i, ntl);
+    it.xi = VT::load(s.xb + (int64_t)it.i * a.ldx);
+    return it;
+  };
+  const int nsteps = (rows_here + per_step - 1) / per_step;
+  Item nxt = prefetch(0);
+  for (int step = 0; step < nsteps; ++step) {
+    const Item cur = nxt;
+    if (step + 1 < nsteps) nxt = prefetch(step + 1);
     typename VT::T acc = VT::zero();
-    walk<VEC, 8>(a.col_c, s.wc, cs, lc, 0, kWave, lane, team, nteams, s.xb, a.ldx, i, ntl, acc);
-    walk<VEC, 8>(s.cd, s.wd, ds, ld, 0, kWave, lane, team, nteams, s.xb, a.ldx, i, ntl, acc);
-    reduce_slots<VEC>(a.ls_log2, acc);
-    if (team == 0 && s.fvalid) finish_row<VEC>(a, s, i, s.dv[i], acc);
-    return;
-  }
-  w -= a.blocks_long;
-  // ---- 64 short rows per wave, one team per row, nteams rows side by side
-  const int64_t first = (w * kWavesPerBlock + wave) * kShortRowsPerWave;
-  if (first >= a.n_short || !(a.parts & 4)) return;
-  int32_t r = 0, c0 = 0, c1 = 0, d0 = 0, d1 = 0;
-  float di = 0.f;
-  if (first + lane < a.n_short) {  // metadata of row `lane` of this wave's 64
-    r = a.rows_short[first + lane];
-    c0 = a.rowptr_c[r]; c1 = a.rowptr_c[r + 1];
-    d0 = s.rpd[r]; d1 = s.rpd[r + 1];
-    di = s.dv[r];
-  }
-  const int rows_here = (int)min((int64_t)kShortRowsPerWave, a.n_short - first);
-  for (int step = 0; step * nteams < rows_here; ++step) {
-    const int li = step * nteams + team;
-    const bool have = li < rows_here;
-    const int src = have ? li : 0;
-    const int32_t i = __shfl(r, src, kWave);
-    const int32_t cs = __shfl(c0, src, kWave);
-    const int32_t ce = __shfl(c1, src, kWave);
-    const int32_t ds = __shfl(d0, src, kWave);
-    const int32_t de = __shfl(d1, src, kWave);
-    const float dii = __shfl(di, src, kWave);
-    if (have) {
-      typename VT::T acc = VT::zero();
-      walk<VEC, 4>(a.col_c, s.wc, cs, ce - cs, team << a.ls_log2, ls, fl, 0, 1, s.xb, a.ldx, i, ntl, acc);
-      walk<VEC, 4>(s.cd, s.wd, ds, de - ds, team << a.ls_log2, ls, fl, 0, 1, s.xb, a.ldx, i, ntl, acc);
-      if (s.fvalid) finish_row<VEC>(a, s, i, dii, acc);
+    if (long_rows) {
+      walk<VEC, UL, FAST>(a.col_c, s.wc, cur.cs, cur.clen, cur.fc, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
+      walk<VEC, UL, FAST>(s.cd, s.wd, cur.ds, cur.dlen, cur.fd, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
+      reduce_slots<VEC>(a.ls_log2, acc);
+      if (team == 0 && s.fvalid) finish_row<VEC>(a, s, cur.i, cur.di, cur.xi, acc);
+    } else if (cur.have) {
+      walk<VEC, US, FAST>(a.col_c, s.wc, cur.cs, cur.clen, cur.fc, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
+      walk<VEC, US, FAST>(s.cd, s.wd, cur.ds, cur.dlen, cur.fd, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
+      if (s.fvalid) finish_row<VEC>(a, s, cur.i, cur.di, cur.xi, acc);
     }
   }
 }
@@ -297,7 +375,8 @@ __global__ __launch_bounds__(kBlock) void k_hub_finish(const AggArgs a) {
     for (int32_t it = it0 + team; it < it1; it += nteams)
       VT::add(acc, VT::load(a.partial + (((int64_t)it * a.nslices + slice) << a.ls_log2) * VEC + fl * VEC));
   reduce_slots<VEC>(a.ls_log2, acc);
-  if (team == 0 && s.fvalid) finish_row<VEC>(a, s, i, s.dv[i], acc);
+  if (team == 0 && s.fvalid)
+    finish_row<VEC>(a, s, i, s.dv[i], VT::load(s.xb + (int64_t)i * a.ldx), acc);
 }
 
 inline int ceil_log2(int64_t x) {
@@ -313,7 +392,15 @@ int launch(const AggArgs &a, hipStream_t st) {
   const int64_t blocks = ((int64_t)a.blocks_items + a.blocks_long + blocks_short) * a.nslices;
   if (blocks >= ((int64_t)1 << 31)) return PIPAD_ERR_TOO_LARGE;
   if (blocks > 0)
-    hipLaunchKernelGGL((k_aggregate<VEC>), dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
+  {
+    // the fast path needs 32-bit byte offsets into a snapshot's matrix and teams of >= 8 lanes
+    const bool fast = a.ls_log2 >= 3 && (int64_t)a.n * a.ldx * 4 < ((int64_t)1 << 32) &&
+                      !options().agg_generic;
+    if (fast)
+      hipLaunchKernelGGL((k_aggregate<VEC, true>), dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
+    else
+      hipLaunchKernelGGL((k_aggregate<VEC, false>), dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
+  }
   if (a.n_hub > 0) {
     const int64_t hb = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock * a.nslices;
     hipLaunchKernelGGL((k_hub_finish<VEC>), dim3((unsigned)hb), dim3(kBlock), 0, st, a);
@@ -349,7 +436,7 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   a.n_items = f->n_items;
   a.n_hub = f->n_hub;
   a.blocks_items = (f->n_items + kWavesPerBlock - 1) / kWavesPerBlock;
-  a.blocks_long = (f->n_long + kWavesPerBlock - 1) / kWavesPerBlock;
+  a.blocks_long = (f->n_long + kWavesPerBlock * kLongRowsPerWave - 1) / (kWavesPerBlock * kLongRowsPerWave);
   a.nt = (int32_t)options().agg_nt;
   a.parts = (int32_t)options().agg_parts;
   bool vec4 = F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
