@@ -30,6 +30,28 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E peak
 
 
+def measured_traffic(workload: str):
+    """HBM bytes per aggregate call from the committed rocprofv3 counter summary of this workload
+    (FETCH_SIZE / WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a
+    plain copy kernel of known size); None when no summary is there."""
+    path = os.path.join(ROOT, "profiles", f"k_aggregate_{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if ":" in line and not line.startswith("#"):
+            key, _, val = line.partition(":")
+            try:
+                vals[key.strip()] = float(val.split()[0])
+            except (ValueError, IndexError):
+                pass
+    try:
+        return int((vals["fetch_size_kib"] * vals["fetch_scale"] +
+                    vals["write_size_kib"] * vals["write_scale"]) * 1024)
+    except KeyError:
+        return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -161,7 +183,7 @@ def main() -> int:
         "aggregate_ms": agg_ms,
         "aggregate_updates_per_s": updates / (agg_ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
                      "kernel": "pipad_frame_aggregate (k_aggregate + k_hub_finish)",
                      "algorithmic_bytes": b_min},
         "paper_context": "PiPAD reports 1.22x-9.57x end-to-end training speedup on a V100 (no absolute "

@@ -109,9 +109,10 @@ def test_small_config_sliding_frames(pipad, first):
 
 @pytest.mark.parametrize("k,F", [(1, 1), (2, 2), (3, 6), (4, 16), (5, 20), (8, 64), (8, 128),
                                  (2, 130), (16, 32), (3, 260), (32, 4), (8, 256), (7, 12)])
-@pytest.mark.parametrize("short_max", [32, 4])
-def test_shapes_and_feature_widths(pipad, k, F, short_max):
+@pytest.mark.parametrize("short_max,generic", [(32, 0), (4, 0), (4, 1)])
+def test_shapes_and_feature_widths(pipad, k, F, short_max, generic):
     pipad.set_option("short_max", short_max)
+    pipad.set_option("agg_generic", generic)
     rng = np.random.default_rng(1000 * k + F)
     n = 333  # several workgroups and a ragged tail
     lists = churned(rng, n, k, 0.03, 0.8)
@@ -240,6 +241,30 @@ def test_invalid_arguments(pipad):
         pipad.frame_build_overlap([(rp, col), (torch.zeros(7, dtype=torch.int32, device="cuda:0"), col)])
     pipad.frame_aggregate(frame, x)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name,check_snapshots", [("large", (0, 3, 7)), ("low-overlap", (0, 7))])
+def test_full_size_frames_in_the_benchmark_configuration(pipad, name, check_snapshots):
+    """The frames bench.py times (N = 1M R-MAT, k = 8, F = 64; N = 500k, F = 128, 40 % churn), in
+    the layout it uses (k separate [N, F] matrices, default options): every CSR entry is compared,
+    and every output element of the listed snapshots."""
+    cfg = synth.CONFIGS[name]
+    s = synth.graphs(cfg.n, cfg.edges, cfg.k, cfg.churn, cfg.model, cfg.params, cfg.seed)
+    dev = "cuda:0"
+    snaps = [(torch.from_numpy(s.rowptr[t]).to(dev), torch.from_numpy(s.col[t]).to(dev))
+             for t in range(cfg.k)]
+    frame = pipad.frame_build_overlap(snaps)
+    coo = [s.coo(t) for t in range(cfg.k)]
+    check_overlap(frame, oracle.overlap(cfg.n, coo))
+    xs = [torch.from_numpy(synth.features(cfg.seed, t, cfg.n, cfg.feat)).to(dev) for t in range(cfg.k)]
+    ys = pipad.frame_aggregate(frame, xs)
+    torch.cuda.synchronize()
+    for t in check_snapshots:
+        _, yd, bound, _ = oracle.aggregate(cfg.n, coo[t][0], coo[t][1], xs[t].cpu().numpy(),
+                                           threads=oracle.hardware_threads())
+        worst = check_y(ys[t].cpu().numpy(), yd, bound, f"{name} snapshot {t}")
+        print(f"{name} snapshot {t}: worst error ratio {worst:.3e} of the 1e-5 budget")
+    frame.close()
 
 
 def test_medium_frame_full_check(pipad):
