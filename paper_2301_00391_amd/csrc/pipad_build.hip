@@ -87,16 +87,12 @@ __device__ inline int32_t row_of_entry(const int32_t *rp, int32_t lo, int32_t hi
   return lo;
 }
 
-// Position of column c in the ascending run col[a, b), or -1.  The search starts at `guess` and
-// gallops outwards, so it costs one load when the guess is right and O(log distance) otherwise:
-// adjacent snapshots differ in few entries, so the offset of a column within its row barely moves
-// from one snapshot to the next.
-__device__ inline int32_t find_near(const int32_t *col, int32_t a, int32_t b, int32_t guess,
-                                    int32_t c) {
-  if (a >= b) return -1;
-  const int32_t g = min(max(guess, a), b - 1);
-  const int32_t v = col[g];
-  if (v == c) return g;
+// Position of column c in the ascending run col[a, b), or -1, given that col[g] == v != c for some
+// g in [a, b).  The search gallops outwards from g, so it costs O(log distance): adjacent
+// snapshots differ in few entries, so the offset of a column within its row barely moves from one
+// snapshot to the next.
+__device__ inline int32_t gallop_from(const int32_t *col, int32_t a, int32_t b, int32_t g,
+                                      int32_t v, int32_t c) {
   int32_t lo, hi;  // the answer, if any, is the lower bound of c within [lo, hi)
   if (v < c) {
     int32_t prev = g, step = 1, cur;
@@ -128,31 +124,76 @@ __device__ inline int32_t find_near(const int32_t *col, int32_t a, int32_t b, in
   return (lo < b && col[lo] == c) ? lo : -1;
 }
 
-// One lane per stored entry of snapshot 0.  The rows of a wave's first and last entry are found
-// with wave-uniform searches; every lane then only searches between those two rows.
-__global__ __launch_bounds__(kBlock) void k_mark(Snaps s, Parts p, int32_t n, int32_t k) {
+// wave_row[w] = row that holds entry 64*w of snapshot 0, for w in [0, ceil(nnz0/64)); one extra
+// slot at the end receives n - 1.  One thread per row writes the (usually zero or one) slots whose
+// entry falls into its row, so k_mark needs no search over the whole row-pointer array.
+__global__ __launch_bounds__(kBlock) void k_wave_rows(const int32_t *rp0, int32_t n, int32_t nnz0,
+                                                       int32_t *wave_row) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  const int32_t a = rp0[i], b = rp0[i + 1];
+  for (int64_t w = ((int64_t)a + kWave - 1) / kWave; w * kWave < b; ++w) wave_row[w] = (int32_t)i;
+  if (i == n - 1) wave_row[((int64_t)nnz0 + kWave - 1) / kWave] = n - 1;
+}
+
+// One lane per stored entry of snapshot 0.  The row of a wave's first entry and an upper bound for
+// the row of its last one come from wave_row; every lane then only searches between those two.
+__global__ __launch_bounds__(kBlock) void k_mark(Snaps s, Parts p, int32_t n, int32_t k,
+                                                  const int32_t *wave_row) {
   const int64_t e64 = (int64_t)blockIdx.x * kBlock + threadIdx.x;  // wave-aligned: 64 | kBlock
   const int32_t nnz0 = s.nnz[0];
   const bool in = e64 < nnz0;
   const int32_t e = in ? (int32_t)e64 : nnz0 - 1;
   const int32_t *rp0 = s.rowptr[0];
-  const int32_t e_first = __builtin_amdgcn_readfirstlane((int32_t)min(e64, (int64_t)nnz0 - 1));
-  const int32_t e_last = min(e_first + kWave - 1, nnz0 - 1);
-  const int32_t r_first = row_of_entry(rp0, 0, n - 1, e_first);
-  const int32_t r_last = row_of_entry(rp0, r_first, n - 1, e_last);
+  const int64_t nwaves0 = ((int64_t)nnz0 + kWave - 1) / kWave;
+  const int64_t w = min(e64 / kWave, nwaves0 - 1);  // waves past the end repeat the last one
+  // (clamped, so that a row-pointer array that is not a valid offset array cannot send the search
+  // out of range: its slots may then be unwritten)
+  const int32_t r_first = min(max(wave_row[w], 0), n - 1);
+  const int32_t r_last = min(max(wave_row[w + 1], r_first), n - 1);  // next wave's first row, or n - 1
   const int32_t i = row_of_entry(rp0, r_first, r_last, e);
   const int32_t c = s.col[0][e];
-  int32_t rel = e - rp0[i];  // offset of the entry within its row; the guess for the next snapshot
+  const int32_t rel = e - rp0[i];  // offset of the entry within its row: the first guess
   bool found = in;
+  // First probe of every snapshot at the same relative offset: all of these loads are independent
+  // of each other, so their latencies overlap.  Only mismatches take the dependent gallop below.
   int32_t pos[PIPAD_MAX_K];
 #pragma unroll
-  for (int t = 1; t < PIPAD_MAX_K; ++t) {
-    pos[t] = 0;
-    if (t < k && found) {
-      const int32_t a = s.rowptr[t][i];
-      const int32_t b = s.rowptr[t][i + 1];
-      const int32_t at = find_near(s.col[t], a, b, a + rel, c);
-      if (at >= 0) { pos[t] = at; rel = at - a; } else { found = false; }
+  for (int t = 0; t < PIPAD_MAX_K; ++t) pos[t] = 0;
+  constexpr int G = 8;  // snapshots probed together (bounds the registers held by the probes)
+#pragma unroll
+  for (int t0 = 1; t0 < PIPAD_MAX_K; t0 += G) {
+    if (t0 < k && found) {
+      int32_t lo[G], hi[G], val[G];
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        const int t = t0 + u;
+        lo[u] = hi[u] = val[u] = 0;
+        if (t < PIPAD_MAX_K && t < k) {
+          lo[u] = s.rowptr[t][i];
+          hi[u] = s.rowptr[t][i + 1];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        const int t = t0 + u;
+        if (t < PIPAD_MAX_K && t < k) {
+          pos[t] = min(max(lo[u] + rel, lo[u]), hi[u] - 1);
+          if (hi[u] > lo[u]) val[u] = s.col[t][pos[t]];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        const int t = t0 + u;
+        if (t < PIPAD_MAX_K && t < k && found) {
+          if (hi[u] <= lo[u]) {
+            found = false;
+          } else if (val[u] != c) {
+            pos[t] = gallop_from(s.col[t], lo[u], hi[u], pos[t], val[u], c);
+            found = pos[t] >= 0;
+          }
+        }
+      }
     }
   }
   const uint64_t word = __ballot(found);
@@ -518,6 +559,8 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   tmp.want(&hubidx, (size_t)scan_len_rows);
   tmp.want(&segoff, (size_t)scan_len_rows);
   tmp.want(&dinv_nk, (size_t)k * n);
+  int32_t *wave_row = nullptr;
+  tmp.want(&wave_row, (size_t)nw[0] + 2);
   tmp.want(&totals, (size_t)PIPAD_MAX_K + 8);
   tmp.want(&dflags, (size_t)64);
   if (alloc) {
@@ -550,8 +593,11 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     if (bad) return fail(PIPAD_ERR_BAD_CSR);
   }
 
-  if (s.nnz[0] > 0)
-    hipLaunchKernelGGL(k_mark, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, n, k);
+  if (s.nnz[0] > 0) {
+    hipLaunchKernelGGL(k_wave_rows, grid1(n, kBlock), dim3(kBlock), 0, st, s.rowptr[0], n, s.nnz[0],
+                       wave_row);
+    hipLaunchKernelGGL(k_mark, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, n, k, wave_row);
+  }
   {
     int32_t max_later = 0;
     for (int t = 1; t < k; ++t) max_later = std::max(max_later, s.nnz[t]);
