@@ -54,6 +54,7 @@ struct AggArgs {
   int32_t blocks_items, blocks_long;  // workgroups per slice for the first two item kinds
   int32_t nt;         // non-temporal hints (bit 0: Y stores, bit 1: index streams)
   int32_t parts;      // timing aid: which kinds of work items run (all in normal use)
+  int32_t sg;         // coalescent kernel: snapshots per lane team (slices are snapshot groups)
   int64_t ldx, ldy;
   const int32_t *rowptr_c, *col_c;
   const float *dinv;
@@ -90,6 +91,18 @@ template <> struct V<4> {
   static __device__ inline T shfl_xor(T v, int m) {
     return make_float4(__shfl_xor(v.x, m, kWave), __shfl_xor(v.y, m, kWave),
                        __shfl_xor(v.z, m, kWave), __shfl_xor(v.w, m, kWave));
+  }
+};
+template <> struct V<2> {
+  using T = float2;
+  static __device__ inline T zero() { return make_float2(0.f, 0.f); }
+  static __device__ inline T load(const float *p) { return *reinterpret_cast<const float2 *>(p); }
+  static __device__ inline void store(float *p, T v, bool) { *reinterpret_cast<float2 *>(p) = v; }
+  static __device__ inline void fma(T &a, float w, T x) { a.x = fmaf(w, x.x, a.x); a.y = fmaf(w, x.y, a.y); }
+  static __device__ inline void add(T &a, T b) { a.x += b.x; a.y += b.y; }
+  static __device__ inline T scale(float w, T a) { return make_float2(w * a.x, w * a.y); }
+  static __device__ inline T shfl_xor(T v, int m) {
+    return make_float2(__shfl_xor(v.x, m, kWave), __shfl_xor(v.y, m, kWave));
   }
 };
 template <> struct V<1> {
@@ -379,6 +392,203 @@ __global__ __launch_bounds__(kBlock) void k_hub_finish(const AggArgs a) {
     finish_row<VEC>(a, s, i, s.dv[i], VT::load(s.xb + (int64_t)i * a.ldx), acc);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Small feature widths (F < 32): the coalescent kernel.
+//
+// When the k feature matrices are handed over as ONE concatenated operand (X[t] = X[0] + t*F, row
+// stride >= k*F: the paper's "coalescent features", Section 4.2) and F is small, one snapshot's row
+// is only a few bytes, which is the "bandwidth unsaturation" case of Section 3.2.  Here a lane team
+// covers the rows of SG consecutive snapshots side by side (SG*F <= 64 columns), so one decoded
+// column index of the overlap part drives ONE contiguous gather for SG snapshots -- the paper's
+// parallel aggregation as it stands, with 64-lane waves: LS = SG*F/VEC lanes per row, 64/LS rows
+// (short rows) or entries (long rows) side by side per wave.  Snapshot groups play the role of
+// slices (consecutive workgroups take consecutive groups).
+// Every lane keeps the scale of its own snapshot: a staged entry is the row offset plus SG scales.
+// The exclusive entries differ per snapshot, so each lane walks the list of its own snapshot.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void k_aggregate_coalescent(const AggArgs a) {
+  using VT = V<VEC>;
+  extern __shared__ uint32_t coal_lds[];  // per wave: 64 row offsets, then 64 x SG scales
+  const int lane = threadIdx.x % kWave;
+  const int wave = threadIdx.x / kWave;
+  const int sg = a.sg;
+  uint32_t *lds_off = coal_lds + wave * (kWave * (1 + sg));
+  float *lds_w = reinterpret_cast<float *>(lds_off + kWave);
+  const int ls = 1 << a.ls_log2;
+  const int fl = lane & (ls - 1);
+  const int team = lane >> a.ls_log2;
+  const int nteams = kWave >> a.ls_log2;
+
+  const int64_t b = blockIdx.x;
+  const int g = (int)(b % a.nslices);  // snapshot group
+  int64_t w = b / a.nslices;
+
+  // this lane's place in the group's row: VEC columns of snapshot t
+  const int pos = fl * VEC;
+  int u = pos / a.F;
+  int t = g * sg + u;
+  const bool valid = pos < sg * a.F && t < a.k;
+  if (!valid) { u = 0; t = g * sg; }
+  const int lane_col = valid ? g * sg * a.F + pos : g * sg * a.F;  // column within the wide row
+  const float *xlane = a.X[0] + lane_col;
+  float *ylane = a.Y[0] + lane_col;
+  const float *dv = a.dinv + (int64_t)t * a.n;
+  const int32_t *rpd = a.rowptr_d[t];
+  const int32_t *cd = a.col_d[t];
+  const float *wd = a.wd[t];
+  const uint32_t row_bytes = (uint32_t)a.ldx * 4u;
+  const char *xbytes = reinterpret_cast<const char *>(a.X[0]);
+  const uint32_t lane_bytes = (uint32_t)lane_col * 4u;
+
+  // Adds row i's entries [c_lo, c_hi) of the overlap part and [d_lo, d_hi) of this lane's own
+  // exclusive part; positions are relative to the row start.
+  auto walk_row = [&](int32_t i, int32_t cs, int32_t c_lo, int32_t c_hi, int32_t d_lo, int32_t d_hi,
+                      int team_base, int team_lanes, int q, int slot, int nslots,
+                      typename VT::T &acc) {
+    for (int32_t base = c_lo; base < c_hi; base += team_lanes) {
+      const int32_t cnt = min(team_lanes, c_hi - base);
+      int32_t c = i;
+      if (q < cnt) c = a.col_c[cs + base + q];
+      lds_off[team_base + q] = (uint32_t)c * row_bytes;
+      for (int v = 0; v < sg; ++v) {
+        const int tv = min(g * sg + v, a.k - 1);
+        lds_w[(team_base + q) * sg + v] = q < cnt ? a.wc[tv][cs + base + q] : 0.f;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      if (team_lanes >= 4 * nslots) {
+        // four gathers in flight; slots past cnt hold (own row, 0), so no bounds checks
+        for (int32_t e0 = 0; e0 < cnt; e0 += 4 * nslots) {
+          uint32_t off[4];
+          float wt[4];
+          typename VT::T x[4];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int32_t e = e0 + v * nslots + slot;
+            off[v] = lds_off[team_base + e];
+            wt[v] = lds_w[(team_base + e) * sg + u];
+          }
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            x[v] = VT::load(reinterpret_cast<const float *>(xbytes + (off[v] + lane_bytes)));
+#pragma unroll
+          for (int v = 0; v < 4; ++v) VT::fma(acc, valid ? wt[v] : 0.f, x[v]);
+        }
+      } else {
+        for (int32_t e = slot; e < cnt; e += nslots) {
+          const uint32_t off = lds_off[team_base + e];
+          const float wt = lds_w[(team_base + e) * sg + u];
+          const typename VT::T x = VT::load(reinterpret_cast<const float *>(xbytes + (off + lane_bytes)));
+          VT::fma(acc, valid ? wt : 0.f, x);
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    if (valid) {
+      const int32_t ds = rpd[i];
+      const int32_t dlen = rpd[i + 1] - ds;
+      const int32_t hi = min(d_hi, dlen);
+      int32_t e = d_lo + slot;
+      for (; e + nslots < hi; e += 2 * nslots) {  // two entries in flight
+        const int32_t j0 = cd[ds + e], j1 = cd[ds + e + nslots];
+        const float w0 = wd[ds + e], w1 = wd[ds + e + nslots];
+        const typename VT::T x0 = VT::load(xlane + (int64_t)j0 * a.ldx);
+        const typename VT::T x1 = VT::load(xlane + (int64_t)j1 * a.ldx);
+        VT::fma(acc, w0, x0);
+        VT::fma(acc, w1, x1);
+      }
+      if (e < hi) VT::fma(acc, wd[ds + e], VT::load(xlane + (int64_t)cd[ds + e] * a.ldx));
+    }
+  };
+  auto finish = [&](int32_t i, typename VT::T acc) {
+    if (!valid) return;
+    const float di = dv[i];
+    VT::fma(acc, di, VT::load(xlane + (int64_t)i * a.ldx));
+    VT::store(ylane + (int64_t)i * a.ldy, VT::scale(di, acc), a.nt & 1);
+  };
+
+  if (w < a.blocks_items) {
+    const int64_t item = w * kWavesPerBlock + wave;
+    if (item >= a.n_items || !(a.parts & 1)) return;
+    const int32_t i = a.item_row[item];
+    const int32_t v0 = a.item_seg[item] * a.seg, v1 = v0 + a.seg;
+    const int32_t cs = a.rowptr_c[i], lc = a.rowptr_c[i + 1] - cs;
+    typename VT::T acc = VT::zero();
+    walk_row(i, cs, min(v0, lc), min(v1, lc), max(v0 - lc, 0), max(v1 - lc, 0), 0, kWave, lane, team,
+             nteams, acc);
+    reduce_slots<VEC>(a.ls_log2, acc);
+    if (team == 0 && valid)
+      VT::store(a.partial + (((int64_t)item * a.nslices + g) << a.ls_log2) * VEC + fl * VEC, acc, false);
+    return;
+  }
+  w -= a.blocks_items;
+  const bool long_rows = w < a.blocks_long;
+  if (!long_rows) w -= a.blocks_long;
+  const int32_t *list = long_rows ? a.rows_long : a.rows_short;
+  const int64_t list_len = long_rows ? a.n_long : a.n_short;
+  const int batch = long_rows ? kLongRowsPerWave : kShortRowsPerWave;
+  const int64_t first = (w * kWavesPerBlock + wave) * batch;
+  if (first >= list_len || !(a.parts & (long_rows ? 2 : 4))) return;
+  const int rows_here = (int)min((int64_t)batch, list_len - first);
+  int32_t r = 0, mc0 = 0, mc1 = 0;
+  if (lane < rows_here) {
+    r = list[first + lane];
+    mc0 = a.rowptr_c[r];
+    mc1 = a.rowptr_c[r + 1];
+  }
+  const int per_step = long_rows ? 1 : nteams;
+  const int nsteps = (rows_here + per_step - 1) / per_step;
+  for (int step = 0; step < nsteps; ++step) {
+    const int li = step * per_step + (long_rows ? 0 : team);
+    const bool have = li < rows_here;
+    const int src = have ? li : 0;
+    const int32_t i = __shfl(r, src, kWave);
+    const int32_t cs = __shfl(mc0, src, kWave);
+    const int32_t ce = __shfl(mc1, src, kWave);  // every lane takes part: sources must be active
+    const int32_t lc = have ? ce - cs : 0;
+    typename VT::T acc = VT::zero();
+    if (long_rows) {
+      walk_row(i, cs, 0, lc, 0, INT32_MAX, 0, kWave, lane, team, nteams, acc);
+      reduce_slots<VEC>(a.ls_log2, acc);
+      if (team == 0) finish(i, acc);
+    } else if (have) {
+      walk_row(i, cs, 0, lc, 0, INT32_MAX, team << a.ls_log2, ls, fl, 0, 1, acc);
+      finish(i, acc);
+    }
+  }
+}
+
+// Hub rows of the coalescent kernel: adds the partial sums of a row in a fixed order.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void k_hub_finish_coalescent(const AggArgs a) {
+  using VT = V<VEC>;
+  const int lane = threadIdx.x % kWave;
+  const int wave = threadIdx.x / kWave;
+  const int ls = 1 << a.ls_log2;
+  const int fl = lane & (ls - 1);
+  const int team = lane >> a.ls_log2;
+  const int nteams = kWave >> a.ls_log2;
+  const int64_t b = blockIdx.x;
+  const int g = (int)(b % a.nslices);
+  const int64_t hr = (b / a.nslices) * kWavesPerBlock + wave;
+  if (hr >= a.n_hub) return;
+  const int pos = fl * VEC;
+  const int t = g * a.sg + pos / a.F;
+  const bool valid = pos < a.sg * a.F && t < a.k;
+  const int32_t i = a.hub_rows[hr];
+  const int32_t it0 = a.hub_item_off[hr], it1 = a.hub_item_off[hr + 1];
+  typename VT::T acc = VT::zero();
+  if (valid)
+    for (int32_t it = it0 + team; it < it1; it += nteams)
+      VT::add(acc, VT::load(a.partial + (((int64_t)it * a.nslices + g) << a.ls_log2) * VEC + fl * VEC));
+  reduce_slots<VEC>(a.ls_log2, acc);
+  if (team == 0 && valid) {
+    const int lane_col = g * a.sg * a.F + pos;
+    const float di = a.dinv[(int64_t)t * a.n + i];
+    VT::fma(acc, di, VT::load(a.X[0] + lane_col + (int64_t)i * a.ldx));
+    VT::store(a.Y[0] + lane_col + (int64_t)i * a.ldy, VT::scale(di, acc), a.nt & 1);
+  }
+}
+
 inline int ceil_log2(int64_t x) {
   int l = 0;
   while (((int64_t)1 << l) < x) ++l;
@@ -404,6 +614,23 @@ int launch(const AggArgs &a, hipStream_t st) {
   if (a.n_hub > 0) {
     const int64_t hb = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock * a.nslices;
     hipLaunchKernelGGL((k_hub_finish<VEC>), dim3((unsigned)hb), dim3(kBlock), 0, st, a);
+  }
+  PIPAD_HIP(hipGetLastError());
+  return PIPAD_OK;
+}
+
+template <int VEC>
+int launch_coalescent(const AggArgs &a, hipStream_t st) {
+  const int64_t blocks_short =
+      ((int64_t)a.n_short + kShortRowsPerWave * kWavesPerBlock - 1) / (kShortRowsPerWave * kWavesPerBlock);
+  const int64_t blocks = ((int64_t)a.blocks_items + a.blocks_long + blocks_short) * a.nslices;
+  if (blocks >= ((int64_t)1 << 31)) return PIPAD_ERR_TOO_LARGE;
+  const size_t lds = (size_t)kWavesPerBlock * kWave * (1 + a.sg) * sizeof(uint32_t);
+  if (blocks > 0)
+    hipLaunchKernelGGL((k_aggregate_coalescent<VEC>), dim3((unsigned)blocks), dim3(kBlock), lds, st, a);
+  if (a.n_hub > 0) {
+    const int64_t hb = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock * a.nslices;
+    hipLaunchKernelGGL((k_hub_finish_coalescent<VEC>), dim3((unsigned)hb), dim3(kBlock), 0, st, a);
   }
   PIPAD_HIP(hipGetLastError());
   return PIPAD_OK;
@@ -449,14 +676,31 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     a.Y[t] = Y[t];
     if ((reinterpret_cast<uintptr_t>(X[t]) | reinterpret_cast<uintptr_t>(Y[t])) & 15u) vec4 = false;
   }
+  // Small F handed over as one concatenated operand: the coalescent kernel (snapshot groups).
+  bool coalescent = F < 32 && f->k > 1 && ldx >= (int64_t)f->k * F && ldy >= (int64_t)f->k * F &&
+                    (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32) && options().agg_coalescent;
+  for (int t = 1; t < f->k && coalescent; ++t)
+    coalescent = X[t] == X[0] + (int64_t)t * F && Y[t] == Y[0] + (int64_t)t * F;
+  int cvec = 1;
+  if (coalescent) {
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(X[0]) | reinterpret_cast<uintptr_t>(Y[0]);
+    if (F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && !(bits & 15u)) cvec = 4;
+    else if (F % 2 == 0 && ldx % 2 == 0 && ldy % 2 == 0 && !(bits & 7u)) cvec = 2;
+    a.sg = std::max(1, std::min<int>(f->k, 64 / F));       // snapshots side by side in a team
+    a.ls_log2 = ceil_log2((a.sg * F + cvec - 1) / cvec);   // lanes per team (<= 64)
+    a.fchunks = 1;
+    a.nslices = (f->k + a.sg - 1) / a.sg;                   // snapshot groups
+  }
   // slice geometry: LS lanes of VEC columns each, at most 64 columns per slice
-  const int vec = vec4 ? 4 : 1;
+  const int vec = coalescent ? cvec : vec4 ? 4 : 1;
   const int max_cols = 64;
   const int cols = std::min(F, max_cols);
-  a.ls_log2 = ceil_log2((cols + vec - 1) / vec);
+  if (!coalescent) {
+    a.ls_log2 = ceil_log2((cols + vec - 1) / vec);
+    a.fchunks = (F + ((1 << a.ls_log2) * vec) - 1) / ((1 << a.ls_log2) * vec);
+    a.nslices = f->k * a.fchunks;
+  }
   const int sw = (1 << a.ls_log2) * vec;
-  a.fchunks = (F + sw - 1) / sw;
-  a.nslices = f->k * a.fchunks;
 
   // scratch for the partial sums of hub segments: n_items x nslices x slice width
   const size_t need = (size_t)f->n_items * (size_t)a.nslices * (size_t)sw;
@@ -481,6 +725,9 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     f->partial_floats = need;
   }
   a.partial = f->partial;
+  if (coalescent)
+    return cvec == 4 ? launch_coalescent<4>(a, st)
+                     : cvec == 2 ? launch_coalescent<2>(a, st) : launch_coalescent<1>(a, st);
   return vec4 ? launch<4>(a, st) : launch<1>(a, st);
 }
 

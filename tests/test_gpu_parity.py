@@ -13,7 +13,7 @@ from _util import check_overlap, check_y, csr_to_coo, to_gpu_snapshots
 pytestmark = pytest.mark.gpu
 
 DEFAULT_OPTIONS = {"short_max": 32, "hub_threshold": 2048, "hub_segment": 1024, "agg_nt": 0,
-                   "agg_parts": 7, "agg_generic": 0}
+                   "agg_parts": 7, "agg_generic": 0, "agg_coalescent": 1}
 
 torch = pytest.importorskip("torch")
 
@@ -131,6 +131,23 @@ def test_row_classes_short_long_hub(pipad, short_max, threshold, segment):
     lists = churned(rng, n, 4, 0.04, 0.7)
     run_case(pipad, n, lists, 16, seed=5)
     run_case(pipad, n, lists, 9, seed=6)
+    run_case(pipad, n, lists, 64, seed=7, layout="wide")
+    # concatenated operand with small F: the coalescent kernel (snapshot groups side by side)
+    run_case(pipad, n, lists, 16, seed=8, layout="wide")
+    run_case(pipad, n, lists, 6, seed=9, layout="wide")
+    run_case(pipad, n, lists, 3, seed=10, layout="wide")
+
+
+@pytest.mark.parametrize("k,F", [(8, 2), (8, 6), (4, 16), (8, 16), (2, 30), (32, 2), (3, 5)])
+@pytest.mark.parametrize("coalescent", [1, 0])
+def test_small_feature_widths_on_the_concatenated_operand(pipad, k, F, coalescent):
+    """The paper's own regime (F = 2 / 6 / 16, Section 5.1): with the concatenated operand the
+    coalescent kernel runs; switched off, the per-snapshot slices must give the same answer."""
+    pipad.set_option("agg_coalescent", coalescent)
+    rng = np.random.default_rng(500 + 10 * k + F)
+    n = 700
+    lists = churned(rng, n, k, 0.02, 0.85)
+    run_case(pipad, n, lists, F, seed=k + F, layout="wide", check_csr=False)
 
 
 def test_directed_patterns(pipad):
