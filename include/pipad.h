@@ -144,6 +144,11 @@ const char *pipad_last_hip_error(void);
  *   "hub_segment"    entries per segment of a split row (default 1024)
  *   "agg_nt"         bit 0: non-temporal stores for Y; bit 1: non-temporal loads for the index and
  *                    scale streams (default 0)
+ *   "agg_generic"    1 forces the bounds-checked kernel with 64-bit addresses (default 0: only for
+ *                    matrices of 4 GB and more)
+ *   "agg_coalescent" kernel for F < 32 on the concatenated operand that gathers the rows of
+ *                    several snapshots with one access: 0 never, 1 automatic (default), 2 whenever
+ *                    the operand allows it
  *   "agg_parts"      timing aid only (results are incomplete unless 7): bit 0 hub segments,
  *                    bit 1 long rows, bit 2 short rows take part (default 7)
  */

@@ -249,13 +249,14 @@ __device__ inline void reduce_slots(int ls_log2, typename V<VEC>::T &acc) {
   for (int m = kWave >> 1; m >= (1 << ls_log2); m >>= 1) V<VEC>::add(acc, V<VEC>::shfl_xor(acc, m));
 }
 
-template <int VEC, bool FAST>
+template <int VEC, bool FAST, int U>
 __global__ __launch_bounds__(kBlock) void k_aggregate(const AggArgs a) {
   using VT = V<VEC>;
   // Row gathers in flight per lane.  Measured on MI355X (N = 1M R-MAT frame): 4 beats 2 and 8 on
-  // both paths; deeper bursts only queue up in front of the L1's miss slots.
-  constexpr int UL = FAST ? 4 : 1;  // wave-wide teams (long rows, hub segments)
-  constexpr int US = FAST ? 4 : 1;  // row-wide teams (short rows)
+  // both paths; deeper bursts only queue up in front of the L1's miss slots.  Teams of fewer
+  // than 4 lanes get U = LS so that U entries per lane group still fit the 64 staged entries.
+  constexpr int UL = FAST ? U : 1;  // wave-wide teams (long rows, hub segments)
+  constexpr int US = FAST ? U : 1;  // row-wide teams (short rows)
   __shared__ Staged staging[kWavesPerBlock][kWave];
   Staged *lds = staging[threadIdx.x / kWave];
   const int lane = threadIdx.x % kWave;
@@ -487,16 +488,23 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_coalescent(const AggArgs a
       const int32_t ds = rpd[i];
       const int32_t dlen = rpd[i + 1] - ds;
       const int32_t hi = min(d_hi, dlen);
-      int32_t e = d_lo + slot;
-      for (; e + nslots < hi; e += 2 * nslots) {  // two entries in flight
-        const int32_t j0 = cd[ds + e], j1 = cd[ds + e + nslots];
-        const float w0 = wd[ds + e], w1 = wd[ds + e + nslots];
-        const typename VT::T x0 = VT::load(xlane + (int64_t)j0 * a.ldx);
-        const typename VT::T x1 = VT::load(xlane + (int64_t)j1 * a.ldx);
-        VT::fma(acc, w0, x0);
-        VT::fma(acc, w1, x1);
+      // four entries in flight; positions past the end read the row's first entry with weight 0
+      for (int32_t e = d_lo + slot; e < hi; e += 4 * nslots) {
+        int32_t j[4];
+        float wt[4];
+        typename VT::T x[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int32_t ev = e + v * nslots;
+          const bool live = ev < hi;
+          j[v] = cd[ds + (live ? ev : e)];
+          wt[v] = live ? wd[ds + ev] : 0.f;
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) x[v] = VT::load(xlane + (int64_t)j[v] * a.ldx);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) VT::fma(acc, wt[v], x[v]);
       }
-      if (e < hi) VT::fma(acc, wd[ds + e], VT::load(xlane + (int64_t)cd[ds + e] * a.ldx));
     }
   };
   auto finish = [&](int32_t i, typename VT::T acc) {
@@ -603,13 +611,18 @@ int launch(const AggArgs &a, hipStream_t st) {
   if (blocks >= ((int64_t)1 << 31)) return PIPAD_ERR_TOO_LARGE;
   if (blocks > 0)
   {
-    // the fast path needs 32-bit byte offsets into a snapshot's matrix and teams of >= 8 lanes
-    const bool fast = a.ls_log2 >= 3 && (int64_t)a.n * a.ldx * 4 < ((int64_t)1 << 32) &&
-                      !options().agg_generic;
-    if (fast)
-      hipLaunchKernelGGL((k_aggregate<VEC, true>), dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
+    // the fast path needs 32-bit byte offsets into a snapshot's matrix; gathers in flight per
+    // lane x lane groups per wave must not exceed the 64 staged entries, so narrow teams get fewer
+    const bool fast = (int64_t)a.n * a.ldx * 4 < ((int64_t)1 << 32) && !options().agg_generic;
+    const dim3 grid((unsigned)blocks), block(kBlock);
+    if (!fast)
+      hipLaunchKernelGGL((k_aggregate<VEC, false, 1>), grid, block, 0, st, a);
+    else if (a.ls_log2 >= 2)
+      hipLaunchKernelGGL((k_aggregate<VEC, true, 4>), grid, block, 0, st, a);
+    else if (a.ls_log2 == 1)
+      hipLaunchKernelGGL((k_aggregate<VEC, true, 2>), grid, block, 0, st, a);
     else
-      hipLaunchKernelGGL((k_aggregate<VEC, false>), dim3((unsigned)blocks), dim3(kBlock), 0, st, a);
+      hipLaunchKernelGGL((k_aggregate<VEC, true, 1>), grid, block, 0, st, a);
   }
   if (a.n_hub > 0) {
     const int64_t hb = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock * a.nslices;
@@ -677,8 +690,16 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     if ((reinterpret_cast<uintptr_t>(X[t]) | reinterpret_cast<uintptr_t>(Y[t])) & 15u) vec4 = false;
   }
   // Small F handed over as one concatenated operand: the coalescent kernel (snapshot groups).
-  bool coalescent = F < 32 && f->k > 1 && ldx >= (int64_t)f->k * F && ldy >= (int64_t)f->k * F &&
-                    (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32) && options().agg_coalescent;
+  // Policy (measured, see the design notes): with one snapshot per XCD a small-F matrix mostly
+  // fits that XCD's L2, so slicing wins unless the matrix is well beyond the L2 and the frame is
+  // dominated by its overlap part (the exclusive parts are walked lane by lane here).
+  int32_t max_delta = 0;
+  for (int t = 0; t < f->k; ++t) max_delta = std::max(max_delta, f->nnz_d[t]);
+  const int64_t mode = options().agg_coalescent;  // 0 never, 1 automatic, 2 whenever possible
+  const bool wanted = mode >= 2 || (mode == 1 && F <= 8 && (int64_t)f->n * F * 4 >= (8 << 20) &&
+                                    (int64_t)f->nnz_c >= 4 * (int64_t)max_delta);
+  bool coalescent = wanted && F < 32 && f->k > 1 && ldx >= (int64_t)f->k * F &&
+                    ldy >= (int64_t)f->k * F && (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32);
   for (int t = 1; t < f->k && coalescent; ++t)
     coalescent = X[t] == X[0] + (int64_t)t * F && Y[t] == Y[0] + (int64_t)t * F;
   int cvec = 1;

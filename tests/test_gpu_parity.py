@@ -89,10 +89,11 @@ def churned(rng, n, k, p, keep, symmetric=True):
     return out
 
 
-@pytest.mark.parametrize("nt", [0, 3])
+@pytest.mark.parametrize("nt,coalescent", [(0, 1), (3, 2)])
 @pytest.mark.parametrize("layout", ["list", "wide"])
-def test_tiny_config(pipad, nt, layout):
+def test_tiny_config(pipad, nt, coalescent, layout):
     pipad.set_option("agg_nt", nt)
+    pipad.set_option("agg_coalescent", coalescent)
     cfg = synth.CONFIGS["tiny"]
     s = synth.make(cfg)
     lists = [(s.rowptr[t], s.col[t]) for t in range(cfg.k)]
@@ -133,13 +134,14 @@ def test_row_classes_short_long_hub(pipad, short_max, threshold, segment):
     run_case(pipad, n, lists, 9, seed=6)
     run_case(pipad, n, lists, 64, seed=7, layout="wide")
     # concatenated operand with small F: the coalescent kernel (snapshot groups side by side)
+    pipad.set_option("agg_coalescent", 2)
     run_case(pipad, n, lists, 16, seed=8, layout="wide")
     run_case(pipad, n, lists, 6, seed=9, layout="wide")
     run_case(pipad, n, lists, 3, seed=10, layout="wide")
 
 
 @pytest.mark.parametrize("k,F", [(8, 2), (8, 6), (4, 16), (8, 16), (2, 30), (32, 2), (3, 5)])
-@pytest.mark.parametrize("coalescent", [1, 0])
+@pytest.mark.parametrize("coalescent", [2, 0])
 def test_small_feature_widths_on_the_concatenated_operand(pipad, k, F, coalescent):
     """The paper's own regime (F = 2 / 6 / 16, Section 5.1): with the concatenated operand the
     coalescent kernel runs; switched off, the per-snapshot slices must give the same answer."""
