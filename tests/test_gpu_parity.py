@@ -249,6 +249,57 @@ def test_validation_rejects_non_canonical_input(pipad):
         assert info.value.status == -2
 
 
+def test_allocator_failure_is_reported_not_fatal(pipad):
+    """A caller allocator that runs dry at any of its calls must give PIPAD_ERR_ALLOC (-3) from
+    build or aggregate, leave no frame behind, and leave the library usable."""
+    import ctypes
+    from paper_2301_00391_amd import binding
+    lib = pipad.load_library()
+    rng = np.random.default_rng(21)
+    n, k = 300, 3
+    lists = churned(rng, n, k, 0.05, 0.8)
+    pipad.set_option("short_max", 2)
+    pipad.set_option("hub_threshold", 6)   # hub rows exist, so aggregate needs scratch
+    pipad.set_option("hub_segment", 4)
+    snaps = [(torch.from_numpy(rp).cuda(), torch.from_numpy(c).cuda()) for rp, c in lists]
+    arr = (binding._Csr * k)()
+    for t, (rp, col) in enumerate(snaps):
+        arr[t].n, arr[t].nnz = n, col.numel()
+        arr[t].rowptr, arr[t].colidx = rp.data_ptr(), col.data_ptr()
+    stream = torch.cuda.current_stream().cuda_stream
+    x = torch.rand((n, k, 8), device="cuda:0")
+    y = torch.empty_like(x)
+    xp = (ctypes.c_void_p * k)(*[x[:, t, :].data_ptr() for t in range(k)])
+    yp = (ctypes.c_void_p * k)(*[y[:, t, :].data_ptr() for t in range(k)])
+    statuses = []
+    for fail_at in range(1, 6):
+        keep, calls = [], [0]
+
+        def alloc(nbytes, _ctx):
+            calls[0] += 1
+            if calls[0] == fail_at:
+                return None
+            buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda:0")
+            keep.append(buf)
+            return buf.data_ptr()
+
+        cb = binding.ALLOC_FN(alloc)
+        out = ctypes.c_void_p()
+        rc = lib.pipad_frame_build_overlap(n, k, arr, 0, ctypes.cast(cb, ctypes.c_void_p), None,
+                                           stream, ctypes.byref(out))
+        if rc == 0:
+            rc = lib.pipad_frame_aggregate(out, 8, xp, k * 8, yp, k * 8, stream)
+            torch.cuda.synchronize()
+            lib.pipad_frame_destroy(out)
+        else:
+            assert out.value is None, "no frame may be handed out on failure"
+        statuses.append(rc)
+    assert statuses[:4] == [-3, -3, -3, -3], statuses  # 3 calls in build, the 4th in aggregate
+    assert statuses[4] == 0
+    # and the library still works afterwards
+    run_case(pipad, n, lists, 8, seed=3)
+
+
 def test_invalid_arguments(pipad):
     rp = torch.zeros(5, dtype=torch.int32, device="cuda:0")
     col = torch.zeros(0, dtype=torch.int32, device="cuda:0")
