@@ -118,6 +118,7 @@ int pipad_frame_shape(const pipad_frame_t *frame, int32_t *n, int32_t *k);
  *        concatenated (coalescent) operand through the same call.
  *   Y    host array of k device pointers, row stride ldy >= F; written exactly once per element
  *        (columns >= F of a wider row are not touched).  Y must not overlap X.
+ *   The current HIP device must be the one the frame was built on (else PIPAD_ERR_INVALID_ARG).
  *   Only enqueues work on `stream`; no host synchronisation.  The first call with a larger k*F
  *   than any before may allocate (and keep) a scratch buffer for the partial sums of very long
  *   rows.  Two aggregations of the SAME frame must not run concurrently (they share that scratch).
@@ -144,6 +145,8 @@ const char *pipad_last_hip_error(void);
  *   "hub_segment"    entries per segment of a split row (default 1024)
  *   "agg_nt"         bit 0: non-temporal stores for Y; bit 1: non-temporal loads for the index and
  *                    scale streams (default 0)
+ *   "slice_cols"     feature columns per slice, at most 64 (default 0: 64, or 32 when that is needed
+ *                    to have at least 8 slices)
  *   "agg_generic"    1 forces the bounds-checked kernel with 64-bit addresses (default 0: only for
  *                    matrices of 4 GB and more)
  *   "agg_coalescent" kernel for F < 32 on the concatenated operand that gathers the rows of

@@ -714,7 +714,12 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   }
   // slice geometry: LS lanes of VEC columns each, at most 64 columns per slice
   const int vec = coalescent ? cvec : vec4 ? 4 : 1;
-  const int max_cols = 64;
+  // With fewer than 8 snapshots a 64-column slice would leave XCDs sharing a slice (and their
+  // L2s caching the same rows twice); 32 columns -- still a whole 128-byte line per gathered row --
+  // doubles the number of slices.
+  int max_cols = 64;
+  if (options().slice_cols > 0) max_cols = (int)std::min<int64_t>(64, options().slice_cols);
+  else if ((int64_t)f->k * ((F + 63) / 64) < 8 && F > 32) max_cols = 32;
   const int cols = std::min(F, max_cols);
   if (!coalescent) {
     a.ls_log2 = ceil_log2((cols + vec - 1) / vec);

@@ -88,6 +88,11 @@ int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *co
       if (!X[t] || !Y[t]) return PIPAD_ERR_INVALID_ARG;
   if ((int64_t)frame->n * ldx >= ((int64_t)1 << 40) || (int64_t)frame->n * ldy >= ((int64_t)1 << 40))
     return PIPAD_ERR_TOO_LARGE;
+  if (frame->n > 0) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return pipad::hip_fail(hipGetLastError(), "hipGetDevice");
+    if (dev != frame->device) return PIPAD_ERR_INVALID_ARG;  // frames are tied to their GPU
+  }
   // the frame's scratch buffer is the only mutable state
   return pipad::aggregate_launch(const_cast<pipad_frame *>(frame), F, X, ldx, Y, ldy,
                                  static_cast<hipStream_t>(stream));
@@ -116,6 +121,7 @@ static int64_t *option_slot(const char *key) {
   if (!std::strcmp(key, "agg_nt")) return &o.agg_nt;
   if (!std::strcmp(key, "agg_parts")) return &o.agg_parts;
   if (!std::strcmp(key, "agg_generic")) return &o.agg_generic;
+  if (!std::strcmp(key, "slice_cols")) return &o.slice_cols;
   if (!std::strcmp(key, "agg_coalescent")) return &o.agg_coalescent;
   if (!std::strcmp(key, "hub_threshold")) return &o.hub_threshold;
   if (!std::strcmp(key, "hub_segment")) return &o.hub_segment;

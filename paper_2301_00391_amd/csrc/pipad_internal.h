@@ -31,6 +31,7 @@ struct Options {
   int64_t hub_segment = 1024;   // entries per segment
   int64_t agg_nt = 0;           // bit 0: non-temporal Y stores, bit 1: non-temporal index streams
   int64_t agg_coalescent = 1;   // small-F coalescent kernel: 0 never, 1 automatic, 2 whenever possible
+  int64_t slice_cols = 0;       // columns per slice (0: automatic, else at most 64)
   int64_t agg_generic = 0;      // 1: force the generic (bounds-checked, 64-bit address) kernel
   int64_t agg_parts = 7;        // timing only: bit 0 hub segments, bit 1 long rows, bit 2 short rows
 };

@@ -13,7 +13,7 @@ from _util import check_overlap, check_y, csr_to_coo, to_gpu_snapshots
 pytestmark = pytest.mark.gpu
 
 DEFAULT_OPTIONS = {"short_max": 32, "hub_threshold": 2048, "hub_segment": 1024, "agg_nt": 0,
-                   "agg_parts": 7, "agg_generic": 0, "agg_coalescent": 1}
+                   "agg_parts": 7, "agg_generic": 0, "agg_coalescent": 1, "slice_cols": 0}
 
 torch = pytest.importorskip("torch")
 
