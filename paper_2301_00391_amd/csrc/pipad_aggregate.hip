@@ -25,14 +25,16 @@
 // Work items of a slice, by row length L = common + longest exclusive row (binned by the build):
 //   short rows  a team of LS lanes (LS * VEC = slice width) per row, 64/LS rows side by side in
 //               a wave, 64 rows per wave; row metadata for the 64 rows is loaded in one go.
-//   long rows   a wave per row; the 64/LS lane teams take different entries and are summed with
-//               cross-lane shuffles.
+//   long rows   a wave per row, 8 rows per wave; the 64/LS lane teams take different entries and
+//               are summed with cross-lane shuffles.
 //   hub rows    cut into segments (the role the paper's sliced CSR plays for load balance,
 //               Section 4.1); a wave per segment writes a partial sum, and a second small kernel
 //               adds the partials of a row in a fixed order.
-// Entries are fetched a team-wide chunk at a time (one coalesced load of indices and scales) and
-// handed to the lanes with ds_bpermute, so the inner loop issues only the 16-byte row gathers
-// (the "vector memory instruction" of Section 4.2), several of them in flight per lane.
+// Entries are fetched a team-wide chunk at a time (one coalesced load of indices and scales),
+// turned into 32-bit row offsets and handed to the lane teams through LDS, so the inner loop
+// issues only the 16-byte row gathers (the "vector memory instruction" of Section 4.2), four of
+// them in flight per lane; the next chunk and the next row's first chunk are requested early.
+// With fewer than 8 slices the slice width drops to 32 columns (still whole 128-byte lines).
 #include <algorithm>
 #include <cstring>
 
