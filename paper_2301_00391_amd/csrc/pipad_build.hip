@@ -13,7 +13,8 @@
 //            over all words.
 //   rowptr   output row pointers are read off the prefix sums at the input row starts.
 //   scatter  every selected entry is written to prefix[word] + (set bits below it in its word),
-//            which keeps the ascending column order of the input (stable compaction).
+//            which keeps the ascending column order of the input (stable compaction); the
+//            per-entry column scales are written alongside.
 //
 // All integer work; the outputs are unique, so they are bit-exact regardless of scheduling (the
 // marks are plain byte stores with one writer each; there are no atomics).
@@ -392,13 +393,54 @@ __global__ __launch_bounds__(kBlock) void k_row_lists(int32_t n, const uint32_t 
 }
 
 // ---- scatter ----------------------------------------------------------------------------------
-// grid.y = part; one lane per stored entry of the part's snapshot.
-// Besides the column index, the column scale dinv_t[column] of the entry is stored: for a common
-// entry once per snapshot, for an exclusive entry for its own snapshot.  dinv_nk is [n][k].
-__global__ __launch_bounds__(kBlock) void k_scatter(Snaps s, Parts p, const uint32_t *pre,
-                                                     const float *dinv_nk, int32_t n, int32_t k) {
-  const int part = blockIdx.y;
-  const int t = part_snapshot(part);
+// Every selected entry is written to prefix[word] + (selected entries below it in its word), which
+// keeps the ascending column order of the input.  Besides the column index, the column scale
+// dinv_t[column] of the entry is stored: for a common entry once per snapshot, for an exclusive
+// entry for its own snapshot.  dinv_nk is [n][k] (one line per node).
+//
+// Common part: one lane per stored entry of snapshot 0 (most of them are selected).
+__global__ __launch_bounds__(kBlock) void k_scatter_common(Snaps s, Parts p, const uint32_t *pre,
+                                                            const float *dinv_nk, int32_t k) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e >= s.nnz[0]) return;
+  const uint32_t w = (uint32_t)(e >> 6), bit = (uint32_t)(e & 63);
+  const uint64_t sel = p.bits[0][w];
+  if (!((sel >> bit) & 1ull)) return;
+  const uint32_t dst = pre[w] - pre[0] + (uint32_t)__popcll(sel & ((1ull << bit) - 1ull));
+  const int32_t c = s.col[0][e];
+  p.col_out[0][dst] = c;
+  for (int u = 0; u < k; ++u) p.wc[u][dst] = dinv_nk[(int64_t)c * k + u];
+}
+
+// Exclusive parts (grid.y = snapshot): usually few entries are selected, so one lane takes a whole
+// 64-entry word and walks its set bits.
+__global__ __launch_bounds__(kBlock) void k_scatter_delta(Snaps s, Parts p, const uint32_t *pre,
+                                                           const float *dinv_nk, int32_t k) {
+  const int t = blockIdx.y;
+  const int part = 1 + t;
+  const uint32_t nw = p.word_off[part + 1] - p.word_off[part];
+  const uint32_t w = blockIdx.x * kBlock + threadIdx.x;
+  if (w >= nw) return;
+  uint64_t sel = selected_word(p, s, part, w);
+  const uint32_t off = p.word_off[part];
+  uint32_t dst = pre[off + w] - pre[off];
+  const int32_t *col = s.col[t] + (int64_t)w * 64;
+  while (sel) {
+    const int bit = __ffsll((unsigned long long)sel) - 1;
+    sel &= sel - 1;
+    const int32_t c = col[bit];
+    p.col_out[part][dst] = c;
+    p.wd[t][dst] = dinv_nk[(int64_t)c * k + t];
+    ++dst;
+  }
+}
+
+// Exclusive parts when most entries are selected (little overlap): one lane per stored entry.
+__global__ __launch_bounds__(kBlock) void k_scatter_delta_dense(Snaps s, Parts p,
+                                                                 const uint32_t *pre,
+                                                                 const float *dinv_nk, int32_t k) {
+  const int t = blockIdx.y;
+  const int part = 1 + t;
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (e >= s.nnz[t]) return;
   const uint32_t w = (uint32_t)(e >> 6), bit = (uint32_t)(e & 63);
@@ -408,11 +450,7 @@ __global__ __launch_bounds__(kBlock) void k_scatter(Snaps s, Parts p, const uint
   const uint32_t dst = pre[off + w] - pre[off] + (uint32_t)__popcll(sel & ((1ull << bit) - 1ull));
   const int32_t c = s.col[t][e];
   p.col_out[part][dst] = c;
-  if (part == 0) {
-    for (int u = 0; u < k; ++u) p.wc[u][dst] = dinv_nk[(int64_t)c * k + u];
-  } else {
-    p.wd[t][dst] = dinv_nk[(int64_t)c * k + t];
-  }
+  p.wd[t][dst] = dinv_nk[(int64_t)c * k + t];
 }
 
 // Collects the data-dependent sizes into one small buffer for a single copy to the host:
@@ -667,11 +705,25 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     p.wd[t] = f->wd[t];
   }
 
-  int32_t max_nnz = 0;
-  for (int t = 0; t < k; ++t) max_nnz = std::max(max_nnz, s.nnz[t]);
-  if (max_nnz > 0)
-    hipLaunchKernelGGL(k_scatter, grid1(max_nnz, kBlock, k + 1), dim3(kBlock), 0, st, s, p, pre,
-                       dinv_nk, n, k);
+  if (s.nnz[0] > 0)
+    hipLaunchKernelGGL(k_scatter_common, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, pre,
+                       dinv_nk, k);
+  {
+    int64_t all = 0, excl = 0;
+    int32_t max_nnz = 0;
+    for (int t = 0; t < k; ++t) {
+      all += s.nnz[t];
+      excl += f->nnz_d[t];
+      max_nnz = std::max(max_nnz, s.nnz[t]);
+    }
+    if (excl * 8 > all) {  // not sparse enough for the per-word walk: a lane per entry
+      hipLaunchKernelGGL(k_scatter_delta_dense, grid1(max_nnz, kBlock, k), dim3(kBlock), 0, st, s, p,
+                         pre, dinv_nk, k);
+    } else if (max_nw > 0) {
+      hipLaunchKernelGGL(k_scatter_delta, grid1(max_nw, kBlock, k), dim3(kBlock), 0, st, s, p, pre,
+                         dinv_nk, k);
+    }
+  }
   hipLaunchKernelGGL(k_row_lists, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, n, shortidx,
                      hubidx, segoff, f->rows_short, f->rows_long, f->hub_rows, f->hub_item_off,
                      f->item_row, f->item_seg);
