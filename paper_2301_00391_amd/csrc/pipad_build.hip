@@ -139,9 +139,25 @@ __global__ __launch_bounds__(kBlock) void k_wave_rows(const int32_t *rp0, int32_
 
 // One lane per stored entry of snapshot 0.  The row of a wave's first entry and an upper bound for
 // the row of its last one come from wave_row; every lane then only searches between those two.
+//
+// Finding the entries' columns in the other snapshots: the 64 entries of a wave are a contiguous
+// stretch of snapshot 0 in (row, column) order, so their matches lie in a contiguous stretch of
+// every other snapshot, about as long and - adjacent snapshots differ little - at about the same
+// offset from the start of the first lane's row.  The wave stages that stretch (kMarkWindow
+// columns per snapshot, two coalesced loads) in LDS and every lane searches its own row's part of
+// the window there.  A lane whose row reaches beyond the window on a side where its column could
+// lie falls back to probing global memory: first at the same relative offset, then galloping.
+constexpr int kMarkGroup = 8;     // snapshots staged together (bounds registers and LDS)
+constexpr int kMarkWindow = 128;  // columns per snapshot staged by a wave
+constexpr int kMarkMargin = 32;   // window columns in front of the first lane's guessed place
+
+template <int KMAX>
 __global__ __launch_bounds__(kBlock) void k_mark(Snaps s, Parts p, int32_t n, int32_t k,
                                                   const int32_t *wave_row) {
+  __shared__ int32_t win[kWavesPerBlock][kMarkGroup][kMarkWindow];
   const int64_t e64 = (int64_t)blockIdx.x * kBlock + threadIdx.x;  // wave-aligned: 64 | kBlock
+  const int lane = threadIdx.x % kWave;
+  const int wv = threadIdx.x / kWave;
   const int32_t nnz0 = s.nnz[0];
   const bool in = e64 < nnz0;
   const int32_t e = in ? (int32_t)e64 : nnz0 - 1;
@@ -156,41 +172,74 @@ __global__ __launch_bounds__(kBlock) void k_mark(Snaps s, Parts p, int32_t n, in
   const int32_t c = s.col[0][e];
   const int32_t rel = e - rp0[i];  // offset of the entry within its row: the first guess
   bool found = in;
-  // First probe of every snapshot at the same relative offset: all of these loads are independent
-  // of each other, so their latencies overlap.  Only mismatches take the dependent gallop below.
-  int32_t pos[PIPAD_MAX_K];
+  int32_t pos[KMAX];
 #pragma unroll
-  for (int t = 0; t < PIPAD_MAX_K; ++t) pos[t] = 0;
-  constexpr int G = 8;  // snapshots probed together (bounds the registers held by the probes)
+  for (int t = 0; t < KMAX; ++t) pos[t] = 0;
+  constexpr int G = kMarkGroup, W = kMarkWindow;
 #pragma unroll
-  for (int t0 = 1; t0 < PIPAD_MAX_K; t0 += G) {
-    if (t0 < k && found) {
-      int32_t lo[G], hi[G], val[G];
+  for (int t0 = 1; t0 < KMAX; t0 += G) {
+    if (t0 < k && __any(found)) {
+      int32_t lo[G], hi[G], P[G];
+      {
+        int32_t v0[G], v1[G];
 #pragma unroll
-      for (int u = 0; u < G; ++u) {
-        const int t = t0 + u;
-        lo[u] = hi[u] = val[u] = 0;
-        if (t < PIPAD_MAX_K && t < k) {
-          lo[u] = s.rowptr[t][i];
-          hi[u] = s.rowptr[t][i + 1];
+        for (int u = 0; u < G; ++u) {
+          const int t = t0 + u;
+          lo[u] = hi[u] = P[u] = 0;
+          v0[u] = v1[u] = INT32_MAX;
+          if (t < KMAX && t < k) {
+            lo[u] = s.rowptr[t][i];
+            hi[u] = s.rowptr[t][i + 1];
+          }
         }
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+          const int t = t0 + u;
+          if (t < KMAX && t < k) {
+            P[u] = max(__shfl(lo[u] + rel, 0) - kMarkMargin, 0);
+            const int32_t a0 = P[u] + lane, a1 = a0 + kWave;
+            if (a0 < s.nnz[t]) v0[u] = s.col[t][a0];
+            if (a1 < s.nnz[t]) v1[u] = s.col[t][a1];
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");  // earlier readers of win are done
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+          win[wv][u][lane] = v0[u];
+          win[wv][u][lane + kWave] = v1[u];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       }
 #pragma unroll
       for (int u = 0; u < G; ++u) {
         const int t = t0 + u;
-        if (t < PIPAD_MAX_K && t < k) {
-          pos[t] = min(max(lo[u] + rel, lo[u]), hi[u] - 1);
-          if (hi[u] > lo[u]) val[u] = s.col[t][pos[t]];
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < G; ++u) {
-        const int t = t0 + u;
-        if (t < PIPAD_MAX_K && t < k && found) {
+        if (t < KMAX && t < k && found) {
           if (hi[u] <= lo[u]) {
             found = false;
-          } else if (val[u] != c) {
-            pos[t] = gallop_from(s.col[t], lo[u], hi[u], pos[t], val[u], c);
+            continue;
+          }
+          const int32_t *wu = win[wv][u];
+          // the row's part of the window holds the match, if there is one, unless the row goes on
+          // in front of the window with columns that may still reach c, or likewise behind it
+          const bool front_ok = lo[u] >= P[u] || (P[u] < hi[u] && wu[0] <= c);
+          const bool back_ok = hi[u] <= P[u] + W || (P[u] + W - 1 >= lo[u] && wu[W - 1] >= c);
+          if (front_ok && back_ok) {
+            int32_t a = max(lo[u], P[u]) - P[u];
+            int32_t b = min(hi[u], P[u] + W) - P[u];
+            const int32_t b0 = b;
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {  // lower bound of c in wu[a, b): at most W + 1 outcomes
+              if (a < b) {
+                const int32_t mid = (a + b) >> 1;
+                if (wu[mid] < c) a = mid + 1; else b = mid;
+              }
+            }
+            found = a < b0 && wu[a] == c;
+            pos[t] = P[u] + a;
+          } else {
+            const int32_t g = min(max(lo[u] + rel, lo[u]), hi[u] - 1);
+            const int32_t v = s.col[t][g];
+            pos[t] = v == c ? g : gallop_from(s.col[t], lo[u], hi[u], g, v, c);
             found = pos[t] >= 0;
           }
         }
@@ -198,12 +247,12 @@ __global__ __launch_bounds__(kBlock) void k_mark(Snaps s, Parts p, int32_t n, in
     }
   }
   const uint64_t word = __ballot(found);
-  if (threadIdx.x % kWave == 0 && in) p.bits[0][e64 >> 6] = word;
+  if (lane == 0 && in) p.bits[0][e64 >> 6] = word;
   if (found) {
     // plain byte stores (every byte has one writer); positions ascend with the lane, so the
     // stores of a wave fall into a few cache lines
 #pragma unroll
-    for (int t = 1; t < PIPAD_MAX_K; ++t)
+    for (int t = 1; t < KMAX; ++t)
       if (t < k) p.flag8[t][pos[t]] = 1;
   }
 }
@@ -634,7 +683,9 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   if (s.nnz[0] > 0) {
     hipLaunchKernelGGL(k_wave_rows, grid1(n, kBlock), dim3(kBlock), 0, st, s.rowptr[0], n, s.nnz[0],
                        wave_row);
-    hipLaunchKernelGGL(k_mark, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, n, k, wave_row);
+    // instances by the largest k they handle: fewer snapshots, fewer registers, more waves per CU
+    auto mark = k <= 8 ? k_mark<8> : k <= 16 ? k_mark<16> : k_mark<PIPAD_MAX_K>;
+    hipLaunchKernelGGL(mark, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, n, k, wave_row);
   }
   {
     int32_t max_later = 0;
