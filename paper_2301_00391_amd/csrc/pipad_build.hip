@@ -257,14 +257,34 @@ __global__ __launch_bounds__(kBlock) void k_mark(Snaps s, Parts p, int32_t n, in
   }
 }
 
-// Packs the byte flags of snapshots 1 .. k-1 into bitmaps (grid.y = t - 1), 64 entries per wave.
+// Packs the byte flags (0 or 1) of snapshots 1 .. k-1 into bitmaps (grid.y = t - 1).  A wave takes
+// 4096 flags in four coalesced 1 KB loads; a lane squeezes its 16 flags into 16 bits and four
+// neighbouring lanes merge into one word.  Flags behind a snapshot's last entry are padding inside
+// the cleared flag area, so they read as zero.
+constexpr int kPackPerWave = 4096;
+
+__device__ inline uint32_t squeeze4(uint32_t x) {  // bytes b0..b3 in {0, 1} -> b0 | b1<<1 | b2<<2 | b3<<3
+  return (x * 0x01020408u) >> 24 & 0xfu;
+}
+
 __global__ __launch_bounds__(kBlock) void k_pack(Snaps s, Parts p) {
   const int t = blockIdx.y + 1;
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   const int32_t nnz = s.nnz[t];
-  const bool set = e < nnz && p.flag8[t][e] != 0;
-  const uint64_t word = __ballot(set);
-  if (threadIdx.x % kWave == 0 && e < nnz) p.bits[t][e >> 6] = word;
+  const int lane = threadIdx.x % kWave;
+  const int64_t base = ((int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave) * kPackPerWave;
+  if (base >= nnz) return;  // whole wave
+#pragma unroll
+  for (int j = 0; j < kPackPerWave / (16 * kWave); ++j) {
+    const int64_t off = base + (int64_t)(j * kWave + lane) * 16;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (off < nnz) v = *reinterpret_cast<const uint4 *>(p.flag8[t] + off);
+    const uint32_t bits16 =
+        squeeze4(v.x) | squeeze4(v.y) << 4 | squeeze4(v.z) << 8 | squeeze4(v.w) << 12;
+    unsigned long long part = (unsigned long long)bits16 << (16 * (lane & 3));
+    part |= __shfl_xor(part, 1);
+    part |= __shfl_xor(part, 2);
+    if ((lane & 3) == 0 && off < nnz) p.bits[t][off >> 6] = part;
+  }
 }
 
 // ---- count ----------------------------------------------------------------------------------
@@ -691,7 +711,8 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     int32_t max_later = 0;
     for (int t = 1; t < k; ++t) max_later = std::max(max_later, s.nnz[t]);
     if (max_later > 0)
-      hipLaunchKernelGGL(k_pack, grid1(max_later, kBlock, k - 1), dim3(kBlock), 0, st, s, p);
+      hipLaunchKernelGGL(k_pack, grid1(max_later, kPackPerWave * kWavesPerBlock, k - 1), dim3(kBlock), 0,
+                         st, s, p);
   }
   uint32_t max_nw = 0;
   for (int t = 0; t < k; ++t) max_nw = std::max(max_nw, nw[t]);
