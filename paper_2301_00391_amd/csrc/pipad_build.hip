@@ -468,6 +468,8 @@ __global__ __launch_bounds__(kBlock) void k_row_lists(int32_t n, const uint32_t 
 // entry for its own snapshot.  dinv_nk is [n][k] (one line per node).
 //
 // Common part: one lane per stored entry of snapshot 0 (most of them are selected).
+// KV > 0: k == 4 * KV, a node's k scales are read as KV 16-byte pieces; KV == 0: any k, one by one.
+template <int KV>
 __global__ __launch_bounds__(kBlock) void k_scatter_common(Snaps s, Parts p, const uint32_t *pre,
                                                             const float *dinv_nk, int32_t k) {
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -478,13 +480,27 @@ __global__ __launch_bounds__(kBlock) void k_scatter_common(Snaps s, Parts p, con
   const uint32_t dst = pre[w] - pre[0] + (uint32_t)__popcll(sel & ((1ull << bit) - 1ull));
   const int32_t c = s.col[0][e];
   p.col_out[0][dst] = c;
-  for (int u = 0; u < k; ++u) p.wc[u][dst] = dinv_nk[(int64_t)c * k + u];
+  if (KV > 0) {
+    const float4 *row = reinterpret_cast<const float4 *>(dinv_nk) + (int64_t)c * KV;
+    float4 v[KV > 0 ? KV : 1];
+#pragma unroll
+    for (int q = 0; q < KV; ++q) v[q] = row[q];
+#pragma unroll
+    for (int q = 0; q < KV; ++q) {
+      p.wc[4 * q + 0][dst] = v[q].x;
+      p.wc[4 * q + 1][dst] = v[q].y;
+      p.wc[4 * q + 2][dst] = v[q].z;
+      p.wc[4 * q + 3][dst] = v[q].w;
+    }
+  } else {
+    for (int u = 0; u < k; ++u) p.wc[u][dst] = dinv_nk[(int64_t)c * k + u];
+  }
 }
 
 // Exclusive parts (grid.y = snapshot): usually few entries are selected, so one lane takes a whole
 // 64-entry word and walks its set bits.
 __global__ __launch_bounds__(kBlock) void k_scatter_delta(Snaps s, Parts p, const uint32_t *pre,
-                                                           const float *dinv_nk, int32_t k) {
+                                                           const float *dinv, int32_t n) {
   const int t = blockIdx.y;
   const int part = 1 + t;
   const uint32_t nw = p.word_off[part + 1] - p.word_off[part];
@@ -494,12 +510,13 @@ __global__ __launch_bounds__(kBlock) void k_scatter_delta(Snaps s, Parts p, cons
   const uint32_t off = p.word_off[part];
   uint32_t dst = pre[off + w] - pre[off];
   const int32_t *col = s.col[t] + (int64_t)w * 64;
+  const float *dinv_t = dinv + (int64_t)t * n;
   while (sel) {
     const int bit = __ffsll((unsigned long long)sel) - 1;
     sel &= sel - 1;
     const int32_t c = col[bit];
     p.col_out[part][dst] = c;
-    p.wd[t][dst] = dinv_nk[(int64_t)c * k + t];
+    p.wd[t][dst] = dinv_t[c];
     ++dst;
   }
 }
@@ -507,7 +524,7 @@ __global__ __launch_bounds__(kBlock) void k_scatter_delta(Snaps s, Parts p, cons
 // Exclusive parts when most entries are selected (little overlap): one lane per stored entry.
 __global__ __launch_bounds__(kBlock) void k_scatter_delta_dense(Snaps s, Parts p,
                                                                  const uint32_t *pre,
-                                                                 const float *dinv_nk, int32_t k) {
+                                                                 const float *dinv, int32_t n) {
   const int t = blockIdx.y;
   const int part = 1 + t;
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -519,7 +536,7 @@ __global__ __launch_bounds__(kBlock) void k_scatter_delta_dense(Snaps s, Parts p
   const uint32_t dst = pre[off + w] - pre[off] + (uint32_t)__popcll(sel & ((1ull << bit) - 1ull));
   const int32_t c = s.col[t][e];
   p.col_out[part][dst] = c;
-  p.wd[t][dst] = dinv_nk[(int64_t)c * k + t];
+  p.wd[t][dst] = dinv[(int64_t)t * n + c];
 }
 
 // Collects the data-dependent sizes into one small buffer for a single copy to the host:
@@ -777,9 +794,11 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     p.wd[t] = f->wd[t];
   }
 
-  if (s.nnz[0] > 0)
-    hipLaunchKernelGGL(k_scatter_common, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, pre,
-                       dinv_nk, k);
+  if (s.nnz[0] > 0) {
+    auto scatter = k == 4 ? k_scatter_common<1> : k == 8 ? k_scatter_common<2>
+                 : k == 16 ? k_scatter_common<4> : k_scatter_common<0>;
+    hipLaunchKernelGGL(scatter, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, pre, dinv_nk, k);
+  }
   {
     int64_t all = 0, excl = 0;
     int32_t max_nnz = 0;
@@ -790,10 +809,10 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     }
     if (excl * 8 > all) {  // not sparse enough for the per-word walk: a lane per entry
       hipLaunchKernelGGL(k_scatter_delta_dense, grid1(max_nnz, kBlock, k), dim3(kBlock), 0, st, s, p,
-                         pre, dinv_nk, k);
+                         pre, f->dinv, n);
     } else if (max_nw > 0) {
       hipLaunchKernelGGL(k_scatter_delta, grid1(max_nw, kBlock, k), dim3(kBlock), 0, st, s, p, pre,
-                         dinv_nk, k);
+                         f->dinv, n);
     }
   }
   hipLaunchKernelGGL(k_row_lists, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, n, shortidx,
