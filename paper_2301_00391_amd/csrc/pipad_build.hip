@@ -168,9 +168,33 @@ __global__ __launch_bounds__(kBlock) void k_mark(Snaps s, Parts p, int32_t n, in
   // out of range: its slots may then be unwritten)
   const int32_t r_first = min(max(wave_row[w], 0), n - 1);
   const int32_t r_last = min(max(wave_row[w + 1], r_first), n - 1);  // next wave's first row, or n - 1
-  const int32_t i = row_of_entry(rp0, r_first, r_last, e);
   const int32_t c = s.col[0][e];
-  const int32_t rel = e - rp0[i];  // offset of the entry within its row: the first guess
+  // Row of the entry: the wave stages the row pointers of its candidate rows in LDS (one round
+  // trip to memory instead of one per step of a search) when they are few enough.
+  int32_t i, row_start;
+  const int32_t nrows = r_last - r_first + 1;
+  if (nrows == 1) {
+    i = r_first;
+    row_start = rp0[i];
+  } else if (nrows < kMarkWindow) {
+    int32_t *rs = win[wv][0];
+    const int32_t a0 = r_first + lane, a1 = a0 + kWave;
+    rs[lane] = a0 <= r_last ? rp0[a0] : INT32_MAX;
+    rs[lane + kWave] = a1 <= r_last ? rp0[a1] : INT32_MAX;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    int32_t cnt = 0;  // number of staged row pointers <= e (at least 1, fewer than kMarkWindow)
+#pragma unroll
+    for (int step = kMarkWindow / 2; step >= 1; step >>= 1)
+      if (rs[cnt + step - 1] <= e) cnt += step;
+    cnt = max(cnt, 1);
+    i = r_first + cnt - 1;
+    row_start = rs[cnt - 1];
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  } else {
+    i = row_of_entry(rp0, r_first, r_last, e);
+    row_start = rp0[i];
+  }
+  const int32_t rel = e - row_start;  // offset of the entry within its row: the first guess
   bool found = in;
   int32_t pos[KMAX];
 #pragma unroll
@@ -210,33 +234,43 @@ __global__ __launch_bounds__(kBlock) void k_mark(Snaps s, Parts p, int32_t n, in
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       }
+      // The row's part of the window holds the match, if there is one, unless the row goes on in
+      // front of the window with columns that may still reach c, or likewise behind it.  The
+      // search is branch-free: window slots in front of the row's part count as smaller than c,
+      // slots behind it as larger, which keeps the predicate monotone over the whole window.
+      uint32_t outside = 0;  // snapshots this lane has to look up in global memory
 #pragma unroll
       for (int u = 0; u < G; ++u) {
         const int t = t0 + u;
-        if (t < KMAX && t < k && found) {
-          if (hi[u] <= lo[u]) {
-            found = false;
-            continue;
-          }
+        if (t < KMAX && t < k) {
           const int32_t *wu = win[wv][u];
-          // the row's part of the window holds the match, if there is one, unless the row goes on
-          // in front of the window with columns that may still reach c, or likewise behind it
-          const bool front_ok = lo[u] >= P[u] || (P[u] < hi[u] && wu[0] <= c);
-          const bool back_ok = hi[u] <= P[u] + W || (P[u] + W - 1 >= lo[u] && wu[W - 1] >= c);
-          if (front_ok && back_ok) {
-            int32_t a = max(lo[u], P[u]) - P[u];
-            int32_t b = min(hi[u], P[u] + W) - P[u];
-            const int32_t b0 = b;
+          const int32_t s0 = max(lo[u], P[u]) - P[u], s1 = min(hi[u], P[u] + W) - P[u];
+          // (bitwise operators on purpose: every LDS read is unconditional, no branches)
+          const int32_t w_first = wu[0], w_last = wu[W - 1];
+          const bool front_ok = (lo[u] >= P[u]) | ((P[u] < hi[u]) & (w_first <= c));
+          const bool back_ok = (hi[u] <= P[u] + W) | ((P[u] + W - 1 >= lo[u]) & (w_last >= c));
+          int32_t a = 0;  // slots counted as smaller than c, capped at W - 1
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {  // lower bound of c in wu[a, b): at most W + 1 outcomes
-              if (a < b) {
-                const int32_t mid = (a + b) >> 1;
-                if (wu[mid] < c) a = mid + 1; else b = mid;
-              }
-            }
-            found = a < b0 && wu[a] == c;
-            pos[t] = P[u] + a;
-          } else {
+          for (int step = W / 2; step >= 1; step >>= 1) {
+            const int32_t idx = a + step - 1;
+            const int32_t v = wu[idx];
+            const bool below = (idx < s0) | ((idx < s1) & (v < c));
+            a += below ? step : 0;
+          }
+          const int32_t v_at = wu[a];
+          const bool hit = (a < s1) & (v_at == c);
+          const bool inwin = front_ok & back_ok;
+          pos[t] = P[u] + a;
+          if (hi[u] <= lo[u]) found = false;
+          else if (!inwin) outside |= 1u << u;
+          else found = found && hit;
+        }
+      }
+      if (outside != 0 && found) {
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+          const int t = t0 + u;
+          if (t < KMAX && t < k && (outside >> u & 1u) && found) {
             const int32_t g = min(max(lo[u] + rel, lo[u]), hi[u] - 1);
             const int32_t v = s.col[t][g];
             pos[t] = v == c ? g : gallop_from(s.col[t], lo[u], hi[u], g, v, c);
