@@ -152,6 +152,25 @@ def test_small_feature_widths_on_the_concatenated_operand(pipad, k, F, coalescen
     run_case(pipad, n, lists, F, seed=k + F, layout="wide", check_csr=False)
 
 
+@pytest.mark.parametrize("k,keep", [(3, 0.97), (8, 0.9), (12, 0.97), (20, 0.5)])
+def test_long_rows_whose_entries_shift_between_snapshots(pipad, k, keep):
+    """Rows of thousands of entries next to short ones: a changed entry moves everything behind
+    it, so the matches of a wave's 64 entries sit at other offsets in the other snapshots (by a
+    few places at keep = 0.97, by hundreds at 0.5, beyond what a wave stages on chip)."""
+    rng = np.random.default_rng(31 * k + int(100 * keep))
+    n = 2500
+    dens = np.full((n, 1), 0.004)
+    dens[rng.choice(n, 6, replace=False)] = 0.8
+    base = rng.random((n, n)) < dens
+    lists = []
+    for _ in range(k):
+        M = base & (rng.random((n, n)) < keep) | (rng.random((n, n)) < dens * (1 - keep))
+        np.fill_diagonal(M, False)
+        rowptr = np.concatenate([[0], np.cumsum(M.sum(axis=1))]).astype(np.int32)
+        lists.append((rowptr, np.nonzero(M)[1].astype(np.int32)))
+    run_case(pipad, n, lists, 4, seed=k)
+
+
 def test_directed_patterns(pipad):
     rng = np.random.default_rng(5)
     lists = churned(rng, 257, 3, 0.05, 0.6, symmetric=False)
