@@ -10,9 +10,14 @@ in HBM: ``pipad_frame_build_overlap`` (overlap + exclusive CSRs, D^-1/2) followe
              aggregate call divided by its duration measured with HIP events on its stream
   cpu_baseline  the CPU oracle timed on this host on a bounded sample of the same frame
 
-Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large] [--epochs E]
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large] [--epochs E] [--cold]
 (--epochs E > 1 runs E aggregations per overlap extraction, the way training reuses one frame's
 decomposition every epoch; the default 1 keeps the whole path in every step.)
+
+Workloads with more snapshots than a frame holds (small, medium) slide the frame by one snapshot
+per step and wrap around (Section 3.3), so the timed steps visit the frames in order.  --cold
+writes 1 GiB of scratch between steps (outside the HIP-event brackets), so that no step finds the
+previous one's data in the caches; its ms_per_step is the sum of the event-bracketed parts.
 """
 from __future__ import annotations
 
@@ -69,8 +74,10 @@ def main() -> int:
     ap.add_argument("--nt", type=int, default=-1)
     ap.add_argument("--hub-threshold", type=int, default=-1)
     ap.add_argument("--hub-segment", type=int, default=-1)
+    ap.add_argument("--cold", action="store_true", help="flush the caches between steps")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--cpu-threads", type=int, default=0, help="oracle threads (0 = all)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
@@ -99,37 +106,53 @@ def main() -> int:
     n, k, F = cfg.n, cfg.k, cfg.feat
 
     t0 = time.time()
-    snaps = synth.graphs(n, cfg.edges, k, cfg.churn, cfg.model, cfg.params, cfg.seed)
-    log(f"[bench] generated {k} snapshots of {args.workload} in {time.time() - t0:.1f}s")
+    S, nframes = cfg.snapshots, cfg.frames
+    snaps = synth.graphs(n, cfg.edges, S, cfg.churn, cfg.model, cfg.params, cfg.seed)
+    log(f"[bench] generated {S} snapshots of {args.workload} in {time.time() - t0:.1f}s")
     t0 = time.time()
-    xh = np.empty((n, k, F), dtype=np.float32)
-    tmp = np.empty((n, F), dtype=np.float32)
-    for t in range(k):
-        synth.features(cfg.seed, t, n, F, out=tmp)
-        xh[:, t, :] = tmp
     gsnaps = [(torch.from_numpy(snaps.rowptr[t]).to(dev), torch.from_numpy(snaps.col[t]).to(dev))
-              for t in range(k)]
-    xw = torch.from_numpy(xh).to(dev)
+              for t in range(S)]
+    xh0 = None  # host copy of snapshot 0's features, for the CPU leg
     if args.layout == "wide":
-        X, Y = xw, torch.empty_like(xw)
+        # one [N, k, F] operand per frame would hold every snapshot k times: the concatenated
+        # layout is timed on frame 0 only
+        nframes = 1
+        xw = torch.empty((n, k, F), dtype=torch.float32, device=dev)
+        for t in range(k):
+            xt = synth.features(cfg.seed, t, n, F)
+            xh0 = xt if t == 0 else xh0
+            xw[:, t, :] = torch.from_numpy(xt).to(dev)
+        Xs, Ys = None, None
+        Yw = torch.empty_like(xw)
     else:
-        X = [xw[:, t, :].contiguous() for t in range(k)]
-        Y = [torch.empty_like(x) for x in X]
-        del xw
+        Xs = []
+        for t in range(S):
+            xt = synth.features(cfg.seed, t, n, F)
+            xh0 = xt if t == 0 else xh0
+            Xs.append(torch.from_numpy(xt).to(dev))
+        Ys = [torch.empty_like(Xs[0]) for _ in range(k)]
+    scratch = torch.empty(1 << 28, dtype=torch.float32, device=dev) if args.cold else None
     torch.cuda.synchronize()
     log(f"[bench] features and upload in {time.time() - t0:.1f}s")
 
-    nnz_t = [int(snaps.col[t].size) for t in range(k)]
-    updates = F * sum(z + n for z in nnz_t)  # per aggregate call
+    nnz_s = [int(snaps.col[t].size) for t in range(S)]
+
+    def frame_inputs(f):
+        if args.layout == "wide":
+            return gsnaps[:k], xw, Yw
+        return gsnaps[f:f + k], Xs[f:f + k], Ys
 
     stream = torch.cuda.current_stream()
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
            torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
 
-    def step(events=None):
+    def step(f, events=None):
+        g, X, Y = frame_inputs(f)
+        if scratch is not None:
+            scratch.fill_(1.0)
         if events:
             events[0].record(stream)
-        frame = pipad.frame_build_overlap(gsnaps)
+        frame = pipad.frame_build_overlap(g)
         if events:
             events[1].record(stream)
         for _ in range(args.epochs):
@@ -138,27 +161,42 @@ def main() -> int:
             events[2].record(stream)
         return frame
 
-    frame = None
-    for _ in range(args.warmup):
-        frame = step()
+    # untimed pass over every frame: sizes of the decompositions (for the algorithmic bytes) and
+    # first-touch effects; then the requested warm-up steps
+    b_min, upd, nnz_c_f, nnz_d_f = [], [], [], []
+    for f in range(nframes):
+        frame = step(f)
+        nnz_c = int(frame.common()[1].numel())
+        nnz_d = [int(frame.delta(t)[1].numel()) for t in range(k)]
+        nnz_c_f.append(nnz_c)
+        nnz_d_f.append(nnz_d)
+        # algorithmic bytes of one aggregate call: X read once, Y written once, every column index
+        # of the overlap and exclusive parts once, the row pointers, D^-1/2
+        b_min.append(4 * k * n * F * 2 + 4 * (nnz_c + sum(nnz_d)) + 4 * (k + 1) * (n + 1) + 4 * k * n)
+        upd.append(F * sum(nnz_s[f + t] + n for t in range(k)))  # per aggregate call
+    for w in range(args.warmup):
+        frame = step((w - args.warmup) % nframes)
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for s in range(args.steps):
-        frame = step(ev[s])
+        frame = step(s % nframes, ev[s])
     torch.cuda.synchronize()
     t_end = time.perf_counter()
-    ms_per_step = (t_end - t_start) * 1e3 / args.steps
-    build_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    agg_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev])) / args.epochs
-
-    # algorithmic bytes of one aggregate call: X read once, Y written once, every column index of
-    # the overlap and exclusive parts once, the row pointers, D^-1/2
-    c_rp, c_col = frame.common()
-    nnz_c = int(c_col.numel())
-    nnz_d = [int(frame.delta(t)[1].numel()) for t in range(k)]
-    b_min = 4 * k * n * F * 2 + 4 * (nnz_c + sum(nnz_d)) + 4 * (k + 1) * (n + 1) + 4 * k * n
-    achieved = b_min / (agg_ms * 1e-3) / 1e9
+    build_all = np.array([e[0].elapsed_time(e[1]) for e in ev])
+    agg_all = np.array([e[1].elapsed_time(e[2]) for e in ev]) / args.epochs
+    build_ms, agg_ms = float(build_all.mean()), float(agg_all.mean())
+    if args.cold:
+        ms_per_step = build_ms + agg_ms * args.epochs
+    else:
+        ms_per_step = (t_end - t_start) * 1e3 / args.steps
+    visited = [s % nframes for s in range(args.steps)]
+    updates = float(np.mean([upd[f] for f in visited]))
+    bytes_min = float(np.mean([b_min[f] for f in visited]))
+    entries_in = float(np.mean([sum(nnz_s[f:f + k]) for f in visited]))
+    achieved = bytes_min / (agg_ms * 1e-3) / 1e9
     value = updates * args.epochs / (ms_per_step * 1e-3)
+    nnz_c, nnz_d = nnz_c_f[0], nnz_d_f[0]
+    nnz_t = nnz_s[:k]
 
     out = {
         "metric": "frame-aggregation edge*feat updates/s (build_overlap + aggregate per frame, k=%d)" % k,
@@ -176,16 +214,20 @@ def main() -> int:
         "config": {"workload": args.workload, "n": n, "k": k, "F": F, "model": None,
                    "generator": cfg.model, "edges_per_snapshot": cfg.edges, "churn": cfg.churn,
                    "seed": cfg.seed, "layout": args.layout, "epochs_per_build": args.epochs,
+                   "frames": nframes, "cache": "cold" if args.cold else "as left by the previous step",
                    "nnz_common": nnz_c, "nnz_exclusive": nnz_d,
                    "overlap_rate": nnz_c / (sum(nnz_t) / k)},
         "frames_per_s": 1e3 / ms_per_step,
         "build_overlap_ms": build_ms,
+        "build_overlap_ms_median": float(np.median(build_all)),
+        "build_input_entries_per_s": entries_in / (build_ms * 1e-3),
         "aggregate_ms": agg_ms,
+        "aggregate_ms_median": float(np.median(agg_all)),
         "aggregate_updates_per_s": updates / (agg_ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
                      "kernel": "pipad_frame_aggregate (k_aggregate + k_hub_finish)",
-                     "algorithmic_bytes": b_min},
+                     "algorithmic_bytes": int(bytes_min)},
         "paper_context": "PiPAD reports 1.22x-9.57x end-to-end training speedup on a V100 (no absolute "
                          "number for this path)",
     }
@@ -193,28 +235,31 @@ def main() -> int:
 
     if not args.no_cpu:
         import oracle
-        threads = oracle.hardware_threads()
-        y_gpu = (Y[:, 0, :] if args.layout == "wide" else Y[0]).cpu().numpy()
+        threads = args.cpu_threads if args.cpu_threads > 0 else oracle.hardware_threads()
+        # the last timed step worked on frame `last`: its snapshot 0 is snapshot `last` of the run
+        last = visited[-1]
+        y_gpu = (Yw[:, 0, :] if args.layout == "wide" else Ys[0]).cpu().numpy()
         done, cpu_s, worst = 0, 0.0, 0.0
-        for t in range(k):
+        for j in range(k):
+            t = last + j
             rows, cols = snaps.coo(t)
-            xt = np.ascontiguousarray(xh[:, t, :])
+            xt = xh0 if t == 0 else synth.features(cfg.seed, t, n, F)
             t1 = time.perf_counter()
             _, yd, bound, used = oracle.aggregate(n, rows, cols, xt, threads=threads,
-                                                  want_bound=(t == 0), want_double=(t == 0))
+                                                  want_bound=(j == 0), want_double=(j == 0))
             cpu_s += time.perf_counter() - t1
             done += 1
-            if t == 0:  # the sample doubles as an end-to-end parity check of snapshot 0
+            if j == 0:  # the sample doubles as an end-to-end parity check of that snapshot
                 err = np.abs(y_gpu.astype(np.float64) - yd)
                 worst = float(np.max(err / np.maximum(bound, 1e-300)))
             if cpu_s >= args.cpu_seconds:
                 break
-        cpu_updates = F * sum(nnz_t[t] + n for t in range(done))
+        cpu_updates = F * sum(nnz_s[last + j] + n for j in range(done))
         out["cpu_baseline"] = {"value": cpu_updates / cpu_s, "unit": "edge*feat updates/s",
                                "cores": used, "kind": "oracle",
-                               "sample": f"per-snapshot aggregation of snapshots 0..{done - 1} of the "
-                                         f"same frame ({cpu_s:.1f} s of oracle time)"}
-        out["parity_snapshot0_worst_err_over_bound"] = worst
+                               "sample": f"per-snapshot aggregation of snapshots {last}..{last + done - 1} "
+                                         f"of the same workload ({cpu_s:.1f} s of oracle time)"}
+        out["parity_first_snapshot_worst_err_over_bound"] = worst
         out["parity_ok"] = bool(worst <= 1e-5)
     print(json.dumps(out), flush=True)
     return 0
