@@ -122,6 +122,9 @@ int pipad_frame_shape(const pipad_frame_t *frame, int32_t *n, int32_t *k);
  *   Only enqueues work on `stream`; no host synchronisation.  The first call with a larger k*F
  *   than any before may allocate (and keep) a scratch buffer for the partial sums of very long
  *   rows.  Two aggregations of the SAME frame must not run concurrently (they share that scratch).
+ *   Apart from that allocation the call consists of kernel launches only, so it can be recorded
+ *   into a HIP graph (stream capture) once an eager call with the same or a larger k*F has sized
+ *   the scratch; an allocation attempted while the stream is capturing fails with PIPAD_ERR_ALLOC.
  *   Results are deterministic: same inputs, same bits.
  */
 int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *const *X,

@@ -223,6 +223,46 @@ def test_library_allocator_and_determinism(pipad):
     assert torch.equal(y1, y2), "same inputs must give the same bits"
 
 
+def test_aggregate_replayed_from_a_hip_graph(pipad):
+    """pipad_frame_aggregate only enqueues kernels (after one eager call has sized the hub
+    scratch), so a training loop can capture it once and replay it.  Every replay, with eager work
+    and synchronisations in between, must reproduce the eager result bit for bit."""
+    pipad.set_option("short_max", 2)
+    pipad.set_option("hub_threshold", 6)
+    pipad.set_option("hub_segment", 4)
+    rng = np.random.default_rng(99)
+    n, k, F = 900, 4, 48
+    lists = churned(rng, n, k, 0.03, 0.8)
+    dev = "cuda:0"
+    snaps = [(torch.from_numpy(rp).to(dev), torch.from_numpy(c).to(dev)) for rp, c in lists]
+    frame = pipad.frame_build_overlap(snaps)
+    X = [torch.from_numpy(synth.features(3, t, n, F)).to(dev) for t in range(k)]
+    Y = [torch.empty_like(x) for x in X]
+    Y_eager = [torch.empty_like(x) for x in X]
+    pipad.frame_aggregate(frame, X, Y)  # eager: sizes the scratch of the hub rows
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pipad.frame_aggregate(frame, X, Y)
+    for replay in range(4):
+        for t in range(k):
+            X[t].copy_(torch.from_numpy(synth.features(100 + replay, t, n, F)))
+        pipad.frame_aggregate(frame, X, Y_eager)
+        torch.cuda.synchronize()
+        for y in Y:
+            y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for t in range(k):
+            assert torch.equal(Y[t], Y_eager[t]), f"replay {replay}, snapshot {t}"
+    # and the replayed result is the right one
+    coo = csr_to_coo(n, *lists[0])
+    x0 = synth.features(103, 0, n, F)
+    _, yd, bound, _ = oracle.aggregate(n, coo[0], coo[1], x0, threads=4)
+    check_y(Y[0].cpu().numpy(), yd, bound, "replayed snapshot 0")
+    frame.close()
+
+
 def test_padded_rows_are_left_alone(pipad):
     """ldy > F: the columns beyond F of Y keep their contents."""
     rng = np.random.default_rng(10)
