@@ -124,7 +124,8 @@ int pipad_frame_shape(const pipad_frame_t *frame, int32_t *n, int32_t *k);
  *   rows.  Two aggregations of the SAME frame must not run concurrently (they share that scratch).
  *   Apart from that allocation the call consists of kernel launches only, so it can be recorded
  *   into a HIP graph (stream capture) once an eager call with the same or a larger k*F has sized
- *   the scratch; an allocation attempted while the stream is capturing fails with PIPAD_ERR_ALLOC.
+ *   the scratch; with the library's own allocator, growing it while the stream is capturing fails
+ *   (PIPAD_ERR_HIP or PIPAD_ERR_ALLOC) and nothing is enqueued.
  *   Results are deterministic: same inputs, same bits.
  */
 int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *const *X,
