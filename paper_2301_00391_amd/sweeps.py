@@ -7,6 +7,7 @@ on the synthetic generator instead of the paper's datasets.
 
   python -m paper_2301_00391_amd.sweeps overlap   # churn x k table
   python -m paper_2301_00391_amd.sweeps features  # F x k table
+  python -m paper_2301_00391_amd.sweeps sliding   # cost per new snapshot when the frame slides by one
 
 Every cell times ``pipad_frame_aggregate`` of one frame of k snapshots and, as the baseline, the
 same k snapshots aggregated one at a time (k frames of a single snapshot each, whose overlap part
@@ -98,6 +99,49 @@ def feature_sweep(dev):
         print(f"| {feat} | " + " | ".join(cells) + " |", flush=True)
 
 
+def sliding_sweep(dev):
+    """Frames that slide by one snapshot (Section 3.3) share k - 1 snapshots with their
+    predecessor.  The aggregation of the raw input features depends on the snapshot alone, so its
+    result can be kept across frames (the paper's inter-frame reuse, Section 4.3); layers whose
+    input depends on the weights need the whole frame again.  Three ways to pay per new snapshot:
+    the whole frame again; only the entering snapshot, as a frame of its own; or - when the
+    snapshots are known in advance, as in training - disjoint groups of k snapshots aggregated as
+    frames once, cost divided by k."""
+    print("cost per new snapshot in ms (build_overlap + aggregate), stride-1 frames\n")
+    print("| workload | whole frame again | entering snapshot alone | disjoint groups of k, per snapshot |")
+    print("|---|---|---|---|")
+    for name in ("small", "medium"):
+        cfg = synth.CONFIGS[name]
+        n, k, feat = cfg.n, cfg.k, cfg.feat
+        snaps = synth.graphs(n, cfg.edges, cfg.snapshots, cfg.churn, cfg.model, cfg.params, cfg.seed)
+        gs = [(torch.from_numpy(snaps.rowptr[t]).to(dev), torch.from_numpy(snaps.col[t]).to(dev))
+              for t in range(cfg.snapshots)]
+        xs = [torch.rand((n, feat), device=dev) * 2 - 1 for _ in range(cfg.snapshots)]
+        ys = [torch.empty_like(x) for x in xs]
+
+        def whole():
+            for f in range(cfg.frames):
+                fr = pipad.frame_build_overlap(gs[f:f + k])
+                pipad.frame_aggregate(fr, xs[f:f + k], ys[f:f + k])
+
+        def entering():
+            for f in range(cfg.frames):
+                t = f + k - 1
+                fr = pipad.frame_build_overlap(gs[t:t + 1])
+                pipad.frame_aggregate(fr, xs[t:t + 1], ys[t:t + 1])
+
+        def groups():
+            for g in range(cfg.snapshots // k):
+                fr = pipad.frame_build_overlap(gs[g * k:(g + 1) * k])
+                pipad.frame_aggregate(fr, xs[g * k:(g + 1) * k], ys[g * k:(g + 1) * k])
+
+        t_whole = _time(whole, 3) / cfg.frames
+        t_enter = _time(entering, 3) / cfg.frames
+        t_group = _time(groups, 3) / (cfg.snapshots // k * k)
+        print(f"| {name} (N = {n}, k = {k}, F = {feat}, {cfg.frames} frames) | {t_whole:.3f} | "
+              f"{t_enter:.3f} | {t_group:.3f} |", flush=True)
+
+
 def main(argv):
     if not torch.cuda.is_available():
         print("sweeps need a GPU", file=sys.stderr)
@@ -108,6 +152,8 @@ def main(argv):
         overlap_sweep(dev)
     elif which == "features":
         feature_sweep(dev)
+    elif which == "sliding":
+        sliding_sweep(dev)
     else:
         print(__doc__, file=sys.stderr)
         return 2
