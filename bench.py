@@ -74,6 +74,8 @@ def main() -> int:
     ap.add_argument("--nt", type=int, default=-1)
     ap.add_argument("--hub-threshold", type=int, default=-1)
     ap.add_argument("--hub-segment", type=int, default=-1)
+    ap.add_argument("--row-stride", default="auto", choices=["auto", "dense"],
+                    help="rows of X: padded to an odd number of 128-byte lines (auto) or F floats")
     ap.add_argument("--cold", action="store_true", help="flush the caches between steps")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -113,6 +115,11 @@ def main() -> int:
     gsnaps = [(torch.from_numpy(snaps.rowptr[t]).to(dev), torch.from_numpy(snaps.col[t]).to(dev))
               for t in range(S)]
     xh0 = None  # host copy of snapshot 0's features, for the CPU leg
+    # HBM layout of X: k separate row-major matrices; by default a row starts every odd number of
+    # 128-byte lines (the padding is never read), which spreads the gathered rows over the channels
+    x_stride = pipad.padded_row_stride(F) if args.row_stride == "auto" else F
+    if args.layout == "wide":
+        x_stride = k * F
     if args.layout == "wide":
         # one [N, k, F] operand per frame would hold every snapshot k times: the concatenated
         # layout is timed on frame 0 only
@@ -129,8 +136,10 @@ def main() -> int:
         for t in range(S):
             xt = synth.features(cfg.seed, t, n, F)
             xh0 = xt if t == 0 else xh0
-            Xs.append(torch.from_numpy(xt).to(dev))
-        Ys = [torch.empty_like(Xs[0]) for _ in range(k)]
+            buf = torch.zeros((n, x_stride), dtype=torch.float32, device=dev)
+            buf[:, :F] = torch.from_numpy(xt).to(dev)
+            Xs.append(buf[:, :F])
+        Ys = [torch.empty((n, F), dtype=torch.float32, device=dev) for _ in range(k)]
     scratch = torch.empty(1 << 28, dtype=torch.float32, device=dev) if args.cold else None
     torch.cuda.synchronize()
     log(f"[bench] features and upload in {time.time() - t0:.1f}s")
@@ -213,7 +222,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": args.workload, "n": n, "k": k, "F": F, "model": None,
                    "generator": cfg.model, "edges_per_snapshot": cfg.edges, "churn": cfg.churn,
-                   "seed": cfg.seed, "layout": args.layout, "epochs_per_build": args.epochs,
+                   "seed": cfg.seed, "layout": args.layout, "x_row_stride_floats": x_stride,
+                   "epochs_per_build": args.epochs,
                    "frames": nframes, "cache": "cold" if args.cold else "as left by the previous step",
                    "nnz_common": nnz_c, "nnz_exclusive": nnz_d,
                    "overlap_rate": nnz_c / (sum(nnz_t) / k)},

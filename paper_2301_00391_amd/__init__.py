@@ -13,5 +13,17 @@ def coalescent_row_bytes(snapshots: int, feat: int) -> int:
     return snapshots * feat * 4
 
 
+def padded_row_stride(feat: int) -> int:
+    """Row stride, in floats, for a feature matrix whose rows are gathered: the smallest odd
+    multiple of 128 bytes that holds ``feat`` floats.  A power-of-two stride ties a row's memory
+    channel to a few bits of the node id; when popular nodes share those bits (R-MAT ids do) their
+    rows crowd onto a few channels.  An odd number of 128-byte lines per row spreads them evenly;
+    the padding is never read."""
+    lines = (feat * 4 + 127) // 128
+    if lines % 2 == 0:
+        lines += 1
+    return lines * 32
+
+
 __all__ = ["Frame", "PipadError", "frame_aggregate", "frame_build_overlap", "get_option",
-           "set_option", "load_library", "coalescent_row_bytes"]
+           "set_option", "load_library", "coalescent_row_bytes", "padded_row_stride"]

@@ -49,3 +49,12 @@ def test_coalescent_row_bytes_match_the_paper(golden_dir):
             continue
         snaps, feat, nbytes = map(int, line.split())
         assert pipad.coalescent_row_bytes(snaps, feat) == nbytes
+
+
+def test_padded_row_stride_is_an_odd_number_of_128_byte_lines():
+    import paper_2301_00391_amd as pipad
+    for feat in (1, 2, 31, 32, 33, 64, 96, 128, 130, 256):
+        stride = pipad.padded_row_stride(feat)
+        assert stride >= feat and stride % 32 == 0 and (stride // 32) % 2 == 1
+        assert stride - feat < 64  # never more than two lines of padding
+    assert pipad.padded_row_stride(64) == 96 and pipad.padded_row_stride(32) == 32

@@ -375,7 +375,8 @@ def test_invalid_arguments(pipad):
 @pytest.mark.parametrize("name,check_snapshots", [("large", (0, 3, 7)), ("low-overlap", (0, 7))])
 def test_full_size_frames_in_the_benchmark_configuration(pipad, name, check_snapshots):
     """The frames bench.py times (N = 1M R-MAT, k = 8, F = 64; N = 500k, F = 128, 40 % churn), in
-    the layout it uses (k separate [N, F] matrices, default options): every CSR entry is compared,
+    the layout it uses (k separate [N, F] matrices whose rows are padded to an odd number of
+    128-byte lines, default options): every CSR entry is compared,
     and every output element of the listed snapshots."""
     cfg = synth.CONFIGS[name]
     s = synth.graphs(cfg.n, cfg.edges, cfg.k, cfg.churn, cfg.model, cfg.params, cfg.seed)
@@ -385,11 +386,17 @@ def test_full_size_frames_in_the_benchmark_configuration(pipad, name, check_snap
     frame = pipad.frame_build_overlap(snaps)
     coo = [s.coo(t) for t in range(cfg.k)]
     check_overlap(frame, oracle.overlap(cfg.n, coo))
-    xs = [torch.from_numpy(synth.features(cfg.seed, t, cfg.n, cfg.feat)).to(dev) for t in range(cfg.k)]
+    stride = pipad.padded_row_stride(cfg.feat)  # bench.py pads the rows of X the same way
+    xs = []
+    for t in range(cfg.k):
+        buf = torch.zeros((cfg.n, stride), dtype=torch.float32, device=dev)
+        buf[:, :cfg.feat] = torch.from_numpy(synth.features(cfg.seed, t, cfg.n, cfg.feat)).to(dev)
+        xs.append(buf[:, :cfg.feat])
     ys = pipad.frame_aggregate(frame, xs)
     torch.cuda.synchronize()
     for t in check_snapshots:
-        _, yd, bound, _ = oracle.aggregate(cfg.n, coo[t][0], coo[t][1], xs[t].cpu().numpy(),
+        _, yd, bound, _ = oracle.aggregate(cfg.n, coo[t][0], coo[t][1],
+                                           np.ascontiguousarray(xs[t].cpu().numpy()),
                                            threads=oracle.hardware_threads())
         worst = check_y(ys[t].cpu().numpy(), yd, bound, f"{name} snapshot {t}")
         print(f"{name} snapshot {t}: worst error ratio {worst:.3e} of the 1e-5 budget")
