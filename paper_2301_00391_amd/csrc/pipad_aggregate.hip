@@ -43,6 +43,8 @@
 namespace pipad {
 namespace {
 
+// Most rows a wave takes one after the other (lane l holds the metadata of row l of the batch).
+// The launch lowers these for small frames, so that the chip still gets enough waves.
 constexpr int kShortRowsPerWave = 64;
 constexpr int kLongRowsPerWave = 8;
 
@@ -54,6 +56,7 @@ struct AggArgs {
   int32_t seg;        // entries per hub segment
   int32_t n_short, n_long, n_items, n_hub;
   int32_t blocks_items, blocks_long;  // workgroups per slice for the first two item kinds
+  int32_t batch_short, batch_long;    // rows per wave
   int32_t nt;         // non-temporal hints (bit 0: Y stores, bit 1: index streams)
   int32_t parts;      // timing aid: which kinds of work items run (all in normal use)
   int32_t sg;         // coalescent kernel: snapshots per lane team (slices are snapshot groups)
@@ -306,7 +309,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const AggArgs a) {
   if (!long_rows) w -= a.blocks_long;
   const int32_t *list = long_rows ? a.rows_long : a.rows_short;
   const int64_t list_len = long_rows ? a.n_long : a.n_short;
-  const int batch = long_rows ? kLongRowsPerWave : kShortRowsPerWave;
+  const int batch = long_rows ? a.batch_long : a.batch_short;
   const int64_t first = (w * kWavesPerBlock + wave) * batch;
   if (first >= list_len || !(a.parts & (long_rows ? 2 : 4))) return;
   const int rows_here = (int)min((int64_t)batch, list_len - first);
@@ -535,7 +538,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_coalescent(const AggArgs a
   if (!long_rows) w -= a.blocks_long;
   const int32_t *list = long_rows ? a.rows_long : a.rows_short;
   const int64_t list_len = long_rows ? a.n_long : a.n_short;
-  const int batch = long_rows ? kLongRowsPerWave : kShortRowsPerWave;
+  const int batch = long_rows ? a.batch_long : a.batch_short;
   const int64_t first = (w * kWavesPerBlock + wave) * batch;
   if (first >= list_len || !(a.parts & (long_rows ? 2 : 4))) return;
   const int rows_here = (int)min((int64_t)batch, list_len - first);
@@ -608,7 +611,7 @@ inline int ceil_log2(int64_t x) {
 template <int VEC>
 int launch(const AggArgs &a, hipStream_t st) {
   const int64_t blocks_short =
-      ((int64_t)a.n_short + kShortRowsPerWave * kWavesPerBlock - 1) / (kShortRowsPerWave * kWavesPerBlock);
+      ((int64_t)a.n_short + a.batch_short * kWavesPerBlock - 1) / (a.batch_short * kWavesPerBlock);
   const int64_t blocks = ((int64_t)a.blocks_items + a.blocks_long + blocks_short) * a.nslices;
   if (blocks >= ((int64_t)1 << 31)) return PIPAD_ERR_TOO_LARGE;
   if (blocks > 0)
@@ -637,7 +640,7 @@ int launch(const AggArgs &a, hipStream_t st) {
 template <int VEC>
 int launch_coalescent(const AggArgs &a, hipStream_t st) {
   const int64_t blocks_short =
-      ((int64_t)a.n_short + kShortRowsPerWave * kWavesPerBlock - 1) / (kShortRowsPerWave * kWavesPerBlock);
+      ((int64_t)a.n_short + a.batch_short * kWavesPerBlock - 1) / (a.batch_short * kWavesPerBlock);
   const int64_t blocks = ((int64_t)a.blocks_items + a.blocks_long + blocks_short) * a.nslices;
   if (blocks >= ((int64_t)1 << 31)) return PIPAD_ERR_TOO_LARGE;
   const size_t lds = (size_t)kWavesPerBlock * kWave * (1 + a.sg) * sizeof(uint32_t);
@@ -678,7 +681,6 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   a.n_items = f->n_items;
   a.n_hub = f->n_hub;
   a.blocks_items = (f->n_items + kWavesPerBlock - 1) / kWavesPerBlock;
-  a.blocks_long = (f->n_long + kWavesPerBlock * kLongRowsPerWave - 1) / (kWavesPerBlock * kLongRowsPerWave);
   a.nt = (int32_t)options().agg_nt;
   a.parts = (int32_t)options().agg_parts;
   bool vec4 = F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
@@ -729,6 +731,26 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     a.nslices = f->k * a.fchunks;
   }
   const int sw = (1 << a.ls_log2) * vec;
+
+  // Rows per wave: the full batches amortise the per-wave set-up on big frames; a small frame gets
+  // shorter ones (down to one row per lane team / per wave), until the launch has a few waves for
+  // every slot of the chip or the batches cannot shrink further.
+  {
+    const int nteams = kWave >> a.ls_log2;
+    const int64_t enough = 4 * 8192;  // waves
+    a.batch_short = kShortRowsPerWave;
+    a.batch_long = kLongRowsPerWave;
+    auto waves = [&]() {
+      return ((int64_t)(f->n_short + a.batch_short - 1) / a.batch_short +
+              (int64_t)(f->n_long + a.batch_long - 1) / a.batch_long + f->n_items) * a.nslices;
+    };
+    while (waves() < enough && (a.batch_short > nteams || a.batch_long > 1)) {
+      if (a.batch_short > nteams) a.batch_short >>= 1;
+      if (a.batch_long > 1) a.batch_long >>= 1;
+    }
+    a.batch_short = std::max(a.batch_short, nteams);
+    a.blocks_long = (f->n_long + kWavesPerBlock * a.batch_long - 1) / (kWavesPerBlock * a.batch_long);
+  }
 
   // scratch for the partial sums of hub segments: n_items x nslices x slice width
   const size_t need = (size_t)f->n_items * (size_t)a.nslices * (size_t)sw;
