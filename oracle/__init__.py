@@ -116,3 +116,27 @@ def aggregate(n: int, rows, cols, X: np.ndarray, threads: int = 1, want_bound: b
     if used < 1:
         raise ValueError("oracle rejected the arguments")
     return Y, Yd, B, used
+
+
+def aggregate_update(n: int, rows, cols, X: np.ndarray, W: np.ndarray,
+                     bias: Optional[np.ndarray] = None, threads: int = 1):
+    """One GCN layer of one snapshot as Eq. 1 composes it: the update (a fully connected layer
+    with weights W[F, Fo] and optional bias[Fo], Section 2.1) applied to the aggregation result,
+    H = (D^-1/2 (A+I) D^-1/2 X) W + bias, in float64 from the float32 inputs.
+
+    Returns ``(H float64[n, Fo], B2 float64[n, Fo])`` with ``B2 = (|A^| |X|) |W| + |bias|``, the
+    scale of the parity tolerance.  The aggregation is :func:`aggregate`; the product is numpy's
+    float64 matmul (a library primitive used as one step)."""
+    if W.ndim != 2 or W.shape[0] != X.shape[1]:
+        raise ValueError("W must be [F, Fo]")
+    _, yd, bound, _ = aggregate(n, rows, cols, X, threads=threads)
+    w64 = W.astype(np.float64)
+    H = yd @ w64
+    B2 = bound @ np.abs(w64)
+    if bias is not None:
+        b64 = np.asarray(bias, dtype=np.float64).reshape(1, -1)
+        if b64.shape[1] != W.shape[1]:
+            raise ValueError("bias must have Fo entries")
+        H = H + b64
+        B2 = B2 + np.abs(b64)
+    return H, B2
