@@ -131,6 +131,33 @@ int pipad_frame_shape(const pipad_frame_t *frame, int32_t *n, int32_t *k);
 int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *const *X,
                           int64_t ldx, float *const *Y, int64_t ldy, void *stream);
 
+/* One GCN layer for every snapshot of the frame: the aggregation above followed by the update of
+ * Eq. 1, a fully connected layer whose weights all snapshots of the frame share (Section 2.1;
+ * "locality-optimized weight reuse", Section 4.2: the weights stay on chip while the rows of all
+ * snapshots pass by):
+ *
+ *      H[t][i, 0:Fo] = ( sum_f A[t][i, f] * W[f, 0:Fo] ) + bias[0:Fo],   A[t] = the Y[t] of
+ *      pipad_frame_aggregate for the same frame, F, X.
+ *
+ *   X, ldx, F   as for pipad_frame_aggregate
+ *   W      device, row-major float [F][Fo], row stride ldw >= Fo
+ *   bias   device float [Fo], or NULL for none
+ *   Fo     output columns, Fo >= 1
+ *   A      host array of k device pointers receiving the aggregation results (row stride lda >= F),
+ *          or NULL when they are not wanted.  NULL is only possible where the update is fused
+ *          into the aggregation kernel: F and Fo multiples of 4 resp. 16 with 16 <= F, Fo <= 64,
+ *          16-byte aligned X (and A) with ldx (lda) a multiple of 4, and a snapshot matrix below
+ *          4 GiB.  Other shapes run the aggregation into A and then a separate multiplication;
+ *          without A they return PIPAD_ERR_INVALID_ARG.
+ *   H      host array of k device pointers, row stride ldh >= Fo; written once per element.
+ *          H, A, X, W must not overlap.
+ *   Stream, device, scratch and determinism rules are those of pipad_frame_aggregate.
+ */
+int pipad_frame_aggregate_update(const pipad_frame_t *frame, int32_t F, const float *const *X,
+                                 int64_t ldx, const float *W, int64_t ldw, const float *bias,
+                                 int32_t Fo, float *const *A, int64_t lda, float *const *H,
+                                 int64_t ldh, void *stream);
+
 /* Releases the frame and every buffer the library allocated itself.  NULL is allowed. */
 void pipad_frame_destroy(pipad_frame_t *frame);
 

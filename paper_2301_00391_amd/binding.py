@@ -50,6 +50,9 @@ SIGNATURES = {
     "pipad_frame_shape": (ctypes.c_int, [_vp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]),
     "pipad_frame_aggregate": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_vp), _i64,
                                              ctypes.POINTER(_vp), _i64, _vp]),
+    "pipad_frame_aggregate_update": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_vp), _i64, _vp, _i64,
+                                                    _vp, _i32, ctypes.POINTER(_vp), _i64,
+                                                    ctypes.POINTER(_vp), _i64, _vp]),
     "pipad_frame_destroy": (None, [_vp]),
     "pipad_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "pipad_last_hip_error": (ctypes.c_char_p, []),
@@ -267,3 +270,40 @@ def frame_aggregate(frame: Frame, X: Features, Y: Optional[Features] = None, str
     with torch.cuda.device(frame.device):
         _check(lib.pipad_frame_aggregate(frame._h, F, xa, ldx, ya, ldy, _stream_handle(stream)))
     return Y
+
+
+def frame_aggregate_update(frame: Frame, X: Features, W: torch.Tensor,
+                           bias: Optional[torch.Tensor] = None, H: Optional[Features] = None,
+                           A: Optional[Features] = None, stream=None) -> Features:
+    """pipad_frame_aggregate_update: H_t = (D_t^-1/2 (A_t + I) D_t^-1/2 X_t) W + bias for every
+    snapshot of the frame.  W is a float32 [F, Fo] device matrix (row stride >= Fo), bias a float32
+    [Fo] device vector or None.  H is allocated (k matrices [n, Fo]) when not given; A, when given,
+    receives the aggregation results.  Only enqueues work on the stream."""
+    lib = load_library()
+    n, k = frame.n, frame.k
+    xp, ldx, F = _operand(X, n, k, "X")
+    if W.dtype != torch.float32 or W.dim() != 2 or W.shape[0] != F or W.stride(1) != 1:
+        raise ValueError("W must be a float32 [F, Fo] matrix with unit column stride")
+    Fo = int(W.shape[1])
+    if bias is not None and (bias.dtype != torch.float32 or bias.dim() != 1 or
+                             bias.shape[0] != Fo or bias.stride(0) != 1):
+        raise ValueError("bias must be a contiguous float32 vector of Fo entries")
+    if H is None:
+        H = [torch.empty((n, Fo), dtype=torch.float32, device=frame.device) for _ in range(k)]
+    hp, ldh, Fh = _operand(H, n, k, "H")
+    if Fh != Fo:
+        raise ValueError("H must have Fo feature columns")
+    xa = (_vp * k)(*xp)
+    ha = (_vp * k)(*hp)
+    aa, lda = None, F
+    if A is not None:
+        ap, lda, Fa = _operand(A, n, k, "A")
+        if Fa != F:
+            raise ValueError("A must have F feature columns")
+        aa = (_vp * k)(*ap)
+    with torch.cuda.device(frame.device):
+        _check(lib.pipad_frame_aggregate_update(
+            frame._h, F, xa, ldx, W.data_ptr(), W.stride(0) if F > 1 else max(Fo, W.stride(0)),
+            bias.data_ptr() if bias is not None else None, Fo, aa, lda, ha, ldh,
+            _stream_handle(stream)))
+    return H

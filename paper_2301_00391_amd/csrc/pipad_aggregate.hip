@@ -71,7 +71,13 @@ struct AggArgs {
   const float *wc[PIPAD_MAX_K];
   const float *wd[PIPAD_MAX_K];
   const float *X[PIPAD_MAX_K];
-  float *Y[PIPAD_MAX_K];
+  float *Y[PIPAD_MAX_K];   // aggregation results (optional when the update is fused in)
+  // fused update: H_t = Y_t W + bias
+  const float *W;          // [F][Fo], row stride ldw
+  const float *bias;       // [Fo] or null
+  int32_t Fo;
+  int64_t ldw, ldh;
+  float *H[PIPAD_MAX_K];
 };
 
 template <int VEC> struct V;
@@ -127,7 +133,8 @@ template <> struct V<1> {
 struct Slice {
   const float *xt;          // X_t (the same for the whole workgroup)
   const float *xb;          // X_t + feature column of this lane
-  float *yb;                // Y_t + feature column of this lane
+  float *yb;                // Y_t + feature column of this lane (null: not wanted)
+  float *ht;                // H_t (fused update only)
   const float *dv;          // dinv_t
   const float *wc, *wd;     // per-entry column scales of the common / exclusive part
   const int32_t *rpd, *cd;  // exclusive CSR of snapshot t
@@ -144,7 +151,8 @@ __device__ inline Slice slice_setup(const AggArgs &a, int slice, int fl, int vec
   const int col = s.fvalid ? s.fcol : 0;  // idle lanes read column 0 and never store
   s.xt = a.X[t];
   s.xb = a.X[t] + col;
-  s.yb = a.Y[t] + col;
+  s.yb = a.Y[t] ? a.Y[t] + col : nullptr;
+  s.ht = a.H[t];
   s.dv = a.dinv + (int64_t)t * a.n;
   s.wc = a.wc[t];
   s.wd = a.wd[t];
@@ -240,6 +248,79 @@ __device__ inline void walk(const int32_t *__restrict__ col, const float *__rest
   }
 }
 
+// ---- fused update (one GCN layer: the fully connected update applied to the aggregation result,
+// Eq. 1; the weights stay on chip for every row of every snapshot a workgroup meets: the
+// weight reuse of Section 4.2) ----------------------------------------------------------------
+// A wave parks finished rows (the slice is the whole row of one snapshot here, K = 4 * LS columns)
+// in a 16-row LDS tile and multiplies a full tile by W with fp32 MFMA 16x16x4 instructions:
+//   A operand  lane (m = lane % 16, g = lane / 16) supplies tile[m][g * KS + ks] at step ks
+//   B operand  the same lane supplies W[g * KS + ks][16 * nt + m]
+// (the instruction sums its four k values over g; KS = K / 4 steps cover every k once), and the
+// result comes back as D[4 * g + r][m] in register r.
+constexpr int kTileRows = 16;
+constexpr int kTileStride = 68;  // floats per tile row: 64 + 4, keeps 16-byte alignment
+
+struct Sink {
+  float *tile;        // this wave's [kTileRows][kTileStride]
+  int32_t *rows;      // this wave's [kTileRows] row ids
+  const float *wl;    // the workgroup's W in LDS: [K][Fo + 1], then the bias as row K
+  int cnt;            // rows parked (wave-uniform)
+};
+
+typedef float mfma_f4 __attribute__((ext_vector_type(4)));
+
+template <int KS>  // k values per lane group = lanes per row
+__device__ inline void sink_flush_ks(const AggArgs &a, const Slice &s, Sink &k, int lane) {
+  const int m = lane & 15, g = lane >> 4;
+  float av[KS];
+#pragma unroll
+  for (int q = 0; q < KS / 4; ++q) {
+    const float4 v = *reinterpret_cast<const float4 *>(k.tile + m * kTileStride + g * KS + 4 * q);
+    av[4 * q + 0] = v.x; av[4 * q + 1] = v.y; av[4 * q + 2] = v.z; av[4 * q + 3] = v.w;
+  }
+  int32_t row[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) row[r] = k.rows[min(4 * g + r, kTileRows - 1)];
+  const int ws = a.Fo + 1;
+  for (int nt = 0; nt < a.Fo / 16; ++nt) {
+    const float *wcol = k.wl + (g * KS) * ws + 16 * nt + m;
+    float bv[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) bv[ks] = wcol[ks * ws];
+    const float b = k.wl[(4 * KS) * ws + 16 * nt + m];  // the bias sits behind W's last row
+    mfma_f4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) d = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ks], bv[ks], d, 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (4 * g + r < k.cnt) s.ht[(int64_t)row[r] * a.ldh + 16 * nt + m] = d[r] + b;
+  }
+}
+
+__device__ inline void sink_flush(const AggArgs &a, const Slice &s, Sink &k, int lane) {
+  if (k.cnt == 0) return;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  switch (a.ls_log2) {
+    case 2: sink_flush_ks<4>(a, s, k, lane); break;
+    case 3: sink_flush_ks<8>(a, s, k, lane); break;
+    default: sink_flush_ks<16>(a, s, k, lane); break;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  k.cnt = 0;
+}
+
+// Self-loop term and row scale; the row goes to the tile (and to Y_t when that is wanted).
+__device__ inline void finish_row_to_sink(const AggArgs &a, const Slice &s, Sink &k, int slot, int fl,
+                                          int32_t i, float di, float4 xi, float4 acc) {
+  using VT = V<4>;
+  VT::fma(acc, di, xi);
+  float4 y = VT::scale(di, acc);
+  if (!s.fvalid) y = make_float4(0.f, 0.f, 0.f, 0.f);  // columns past F pad K with zeros
+  else if (s.yb) VT::store(s.yb + (int64_t)i * a.ldy, y, a.nt & 1);
+  *reinterpret_cast<float4 *>(k.tile + slot * kTileStride + fl * 4) = y;
+  if (fl == 0) k.rows[slot] = i;
+}
+
 // Self-loop term, row scale, store.
 template <int VEC>
 __device__ inline void finish_row(const AggArgs &a, const Slice &s, int32_t i, float di,
@@ -254,9 +335,30 @@ __device__ inline void reduce_slots(int ls_log2, typename V<VEC>::T &acc) {
   for (int m = kWave >> 1; m >= (1 << ls_log2); m >>= 1) V<VEC>::add(acc, V<VEC>::shfl_xor(acc, m));
 }
 
-template <int VEC, bool FAST, int U>
-__global__ __launch_bounds__(kBlock) void k_aggregate(const AggArgs a) {
+template <int VEC, bool FAST, int U, bool UPD>
+__device__ __forceinline__ void aggregate_body(const AggArgs &a) {
   using VT = V<VEC>;
+  static_assert(!UPD || (VEC == 4 && FAST), "the fused update rides on the fast float4 path");
+  extern __shared__ __align__(16) float upd_lds[];  // UPD: W [K][Fo + 1], then the waves' tiles and row ids
+  Sink sink;
+  if (UPD) {
+    const int K = 4 << a.ls_log2, ws = a.Fo + 1;
+    for (int idx = threadIdx.x; idx < K * a.Fo; idx += kBlock) {
+      const int kk = idx / a.Fo, o = idx - kk * a.Fo;
+      upd_lds[kk * ws + o] = kk < a.F ? a.W[(int64_t)kk * a.ldw + o] : 0.f;
+    }
+    // row K: the bias (a load from global memory inside the flush would make the wave wait for
+    // every gather it has in flight)
+    for (int o = threadIdx.x; o < a.Fo; o += kBlock) upd_lds[K * ws + o] = a.bias ? a.bias[o] : 0.f;
+    const int w_floats = ((K + 1) * ws + 3) & ~3;
+    float *tiles = upd_lds + w_floats;
+    sink.wl = upd_lds;
+    sink.tile = tiles + (threadIdx.x / kWave) * kTileRows * kTileStride;
+    sink.rows = reinterpret_cast<int32_t *>(tiles + kWavesPerBlock * kTileRows * kTileStride) +
+                (threadIdx.x / kWave) * kTileRows;
+    sink.cnt = 0;
+    __syncthreads();  // before any wave leaves
+  }
   // Row gathers in flight per lane.  Measured on MI355X (N = 1M R-MAT frame): 4 beats 2 and 8 on
   // both paths; deeper bursts only queue up in front of the L1's miss slots.  Teams of fewer
   // than 4 lanes get U = LS so that U entries per lane group still fit the 64 staged entries.
@@ -356,26 +458,60 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const AggArgs a) {
   Item nxt = prefetch(0);
   for (int step = 0; step < nsteps; ++step) {
     const Item cur = nxt;
+    const int rows_now = long_rows ? 1 : min(per_step, rows_here - step * per_step);
+    if constexpr (UPD) {
+      // Make room in the tile before the next rows' loads are requested: the multiplication then
+      // runs while nothing but this step's (already needed) data is in flight, and its registers
+      // do not compete with the prefetched rows.
+      if (sink.cnt + rows_now > kTileRows) sink_flush(a, s, sink, lane);
+    }
     if (step + 1 < nsteps) nxt = prefetch(step + 1);
     typename VT::T acc = VT::zero();
     if (long_rows) {
       walk<VEC, UL, FAST>(a.col_c, s.wc, cur.cs, cur.clen, cur.fc, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
       walk<VEC, UL, FAST>(s.cd, s.wd, cur.ds, cur.dlen, cur.fd, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
       reduce_slots<VEC>(a.ls_log2, acc);
-      if (team == 0 && s.fvalid) finish_row<VEC>(a, s, cur.i, cur.di, cur.xi, acc);
-    } else if (cur.have) {
-      walk<VEC, US, FAST>(a.col_c, s.wc, cur.cs, cur.clen, cur.fc, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
-      walk<VEC, US, FAST>(s.cd, s.wd, cur.ds, cur.dlen, cur.fd, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
-      if (s.fvalid) finish_row<VEC>(a, s, cur.i, cur.di, cur.xi, acc);
+      if constexpr (UPD) {
+        if (team == 0) finish_row_to_sink(a, s, sink, sink.cnt, fl, cur.i, cur.di, cur.xi, acc);
+        sink.cnt += 1;
+      } else {
+        if (team == 0 && s.fvalid) finish_row<VEC>(a, s, cur.i, cur.di, cur.xi, acc);
+      }
+    } else {
+      if (cur.have) {
+        walk<VEC, US, FAST>(a.col_c, s.wc, cur.cs, cur.clen, cur.fc, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
+        walk<VEC, US, FAST>(s.cd, s.wd, cur.ds, cur.dlen, cur.fd, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
+      }
+      if constexpr (UPD) {
+        if (cur.have) finish_row_to_sink(a, s, sink, sink.cnt + team, fl, cur.i, cur.di, cur.xi, acc);
+        sink.cnt += rows_now;  // teams 0 .. rows_now - 1 had a row
+      } else {
+        if (cur.have && s.fvalid) finish_row<VEC>(a, s, cur.i, cur.di, cur.xi, acc);
+      }
     }
   }
+  if constexpr (UPD) sink_flush(a, s, sink, lane);
+}
+
+template <int VEC, bool FAST, int U>
+__global__ __launch_bounds__(kBlock) void k_aggregate(const AggArgs a) {
+  aggregate_body<VEC, FAST, U, false>(a);
+}
+
+// The same walk with the update fused in.  Its tile bookkeeping would push the register count
+// just past the limit for four waves per SIMD, which the gathers need to hide their latency.
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void k_aggregate_update(const AggArgs a) {
+  aggregate_body<4, true, 4, true>(a);
 }
 
 // Adds the partial sums of every hub row in a fixed order and finishes the row.
 // One wave per (hub row, slice); the lane teams stride over the row's segments.
-template <int VEC>
+// UPD: the slice is the whole row; the few hub rows are multiplied by W with plain FMAs.
+template <int VEC, bool UPD = false>
 __global__ __launch_bounds__(kBlock) void k_hub_finish(const AggArgs a) {
   using VT = V<VEC>;
+  __shared__ __align__(16) float yrow[UPD ? kWavesPerBlock : 1][UPD ? kWave : 1];
   const int lane = threadIdx.x % kWave;
   const int wave = threadIdx.x / kWave;
   const int ls = 1 << a.ls_log2;
@@ -394,8 +530,56 @@ __global__ __launch_bounds__(kBlock) void k_hub_finish(const AggArgs a) {
     for (int32_t it = it0 + team; it < it1; it += nteams)
       VT::add(acc, VT::load(a.partial + (((int64_t)it * a.nslices + slice) << a.ls_log2) * VEC + fl * VEC));
   reduce_slots<VEC>(a.ls_log2, acc);
-  if (team == 0 && s.fvalid)
-    finish_row<VEC>(a, s, i, s.dv[i], VT::load(s.xb + (int64_t)i * a.ldx), acc);
+  if constexpr (UPD) {
+    if (team == 0) {
+      const float di = s.dv[i];
+      VT::fma(acc, di, VT::load(s.xb + (int64_t)i * a.ldx));
+      typename VT::T y = VT::scale(di, acc);
+      if (!s.fvalid) y = VT::zero();
+      else if (s.yb) VT::store(s.yb + (int64_t)i * a.ldy, y, a.nt & 1);
+      *reinterpret_cast<typename VT::T *>(&yrow[wave][fl * VEC]) = y;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    for (int o = lane; o < a.Fo; o += kWave) {
+      float h = a.bias ? a.bias[o] : 0.f;
+      for (int f = 0; f < a.F; ++f) h = fmaf(yrow[wave][f], a.W[(int64_t)f * a.ldw + o], h);
+      s.ht[(int64_t)i * a.ldh + o] = h;
+    }
+  } else {
+    if (team == 0 && s.fvalid)
+      finish_row<VEC>(a, s, i, s.dv[i], VT::load(s.xb + (int64_t)i * a.ldx), acc);
+  }
+}
+
+// Update alone, for shapes the fused kernel does not take: H_t = Y_t W + bias from the stored
+// aggregation results.  A wave owns 16 rows of one snapshot; fp32 MFMA 16x16x4 with the usual
+// operand layout (lane (m, g): A[m][k0 + g], B[k0 + g][16 nt + m]; D[4 g + r][m] in register r).
+__global__ __launch_bounds__(kBlock) void k_update(const AggArgs a) {
+  const int lane = threadIdx.x % kWave;
+  const int64_t tiles = ((int64_t)a.n + 15) / 16;
+  const int64_t id = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  if (id >= tiles * a.k) return;
+  const int t = (int)(id / tiles);
+  const int64_t row0 = (id - t * tiles) * 16;
+  const int m = lane & 15, g = lane >> 4;
+  const int64_t row = row0 + m;
+  const float *arow = a.Y[t] + min(row, (int64_t)a.n - 1) * a.ldy;
+  for (int nt = 0; nt * 16 < a.Fo; ++nt) {
+    const int col = 16 * nt + m;
+    mfma_f4 d = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < a.F; k0 += 4) {
+      const int kk = k0 + g;
+      const float av = (kk < a.F && row < a.n) ? arow[kk] : 0.f;
+      const float bv = (kk < a.F && col < a.Fo) ? a.W[(int64_t)kk * a.ldw + col] : 0.f;
+      d = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, d, 0, 0, 0);
+    }
+    const float bias = (a.bias && col < a.Fo) ? a.bias[col] : 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int64_t orow = row0 + 4 * g + r;
+      if (orow < a.n && col < a.Fo) a.H[t][orow * a.ldh + col] = d[r] + bias;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -608,8 +792,16 @@ inline int ceil_log2(int64_t x) {
   return l;
 }
 
+// LDS of the fused-update kernel: W [K][Fo + 1] and the bias, one tile and 16 row ids per wave.
+inline size_t update_lds_bytes(const AggArgs &a) {
+  const size_t K = (size_t)4 << a.ls_log2;
+  const size_t w_floats = ((K + 1) * (a.Fo + 1) + 3) & ~(size_t)3;  // W and, as row K, the bias
+  return (w_floats + (size_t)kWavesPerBlock * kTileRows * kTileStride) * sizeof(float) +
+         (size_t)kWavesPerBlock * kTileRows * sizeof(int32_t);
+}
+
 template <int VEC>
-int launch(const AggArgs &a, hipStream_t st) {
+int launch(const AggArgs &a, hipStream_t st, bool fused_update = false) {
   const int64_t blocks_short =
       ((int64_t)a.n_short + a.batch_short * kWavesPerBlock - 1) / (a.batch_short * kWavesPerBlock);
   const int64_t blocks = ((int64_t)a.blocks_items + a.blocks_long + blocks_short) * a.nslices;
@@ -620,6 +812,18 @@ int launch(const AggArgs &a, hipStream_t st) {
     // lane x lane groups per wave must not exceed the 64 staged entries, so narrow teams get fewer
     const bool fast = (int64_t)a.n * a.ldx * 4 < ((int64_t)1 << 32) && !options().agg_generic;
     const dim3 grid((unsigned)blocks), block(kBlock);
+    if constexpr (VEC == 4) {
+      if (fused_update) {
+        if (!fast || a.ls_log2 < 2) return PIPAD_ERR_INVALID_ARG;  // the caller checked the shape
+        hipLaunchKernelGGL(k_aggregate_update, grid, block, update_lds_bytes(a), st, a);
+        if (a.n_hub > 0) {
+          const int64_t hb = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock * a.nslices;
+          hipLaunchKernelGGL((k_hub_finish<4, true>), dim3((unsigned)hb), dim3(kBlock), 0, st, a);
+        }
+        PIPAD_HIP(hipGetLastError());
+        return PIPAD_OK;
+      }
+    }
     if (!fast)
       hipLaunchKernelGGL((k_aggregate<VEC, false, 1>), grid, block, 0, st, a);
     else if (a.ls_log2 >= 2)
@@ -657,7 +861,7 @@ int launch_coalescent(const AggArgs &a, hipStream_t st) {
 }  // namespace
 
 int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t ldx,
-                     float *const *Y, int64_t ldy, hipStream_t st) {
+                     float *const *Y, int64_t ldy, hipStream_t st, const UpdateSpec *upd) {
   if (f->n == 0) return PIPAD_OK;
   AggArgs a;
   std::memset(&a, 0, sizeof(a));
@@ -690,8 +894,23 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     a.wc[t] = f->wc[t];
     a.wd[t] = f->wd[t];
     a.X[t] = X[t];
-    a.Y[t] = Y[t];
-    if ((reinterpret_cast<uintptr_t>(X[t]) | reinterpret_cast<uintptr_t>(Y[t])) & 15u) vec4 = false;
+    a.Y[t] = Y ? Y[t] : nullptr;
+    if ((reinterpret_cast<uintptr_t>(X[t]) | reinterpret_cast<uintptr_t>(a.Y[t])) & 15u) vec4 = false;
+  }
+  // The update rides inside the aggregation kernel when a slice is a whole row of one snapshot
+  // (F <= 64 in float4 pieces), W fits next to the row tiles in LDS and the fast addressing
+  // applies; other shapes aggregate into Y first and multiply afterwards.
+  bool fused = false;
+  if (upd) {
+    a.W = upd->W;
+    a.bias = upd->bias;
+    a.Fo = upd->Fo;
+    a.ldw = upd->ldw;
+    a.ldh = upd->ldh;
+    for (int t = 0; t < f->k; ++t) a.H[t] = upd->H[t];
+    fused = vec4 && F >= 16 && F <= 64 && upd->Fo >= 16 && upd->Fo <= 64 && upd->Fo % 16 == 0 &&
+            (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32) && !options().agg_generic;
+    if (!fused && !Y) return PIPAD_ERR_INVALID_ARG;  // the two-step form needs Y as its workspace
   }
   // Small F handed over as one concatenated operand: the coalescent kernel (snapshot groups).
   // Policy (measured, see the design notes): with one snapshot per XCD a small-F matrix mostly
@@ -702,7 +921,7 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   const int64_t mode = options().agg_coalescent;  // 0 never, 1 automatic, 2 whenever possible
   const bool wanted = mode >= 2 || (mode == 1 && F <= 8 && (int64_t)f->n * F * 4 >= (8 << 20) &&
                                     (int64_t)f->nnz_c >= 4 * (int64_t)max_delta);
-  bool coalescent = wanted && F < 32 && f->k > 1 && ldx >= (int64_t)f->k * F &&
+  bool coalescent = wanted && !upd && F < 32 && f->k > 1 && ldx >= (int64_t)f->k * F &&
                     ldy >= (int64_t)f->k * F && (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32);
   for (int t = 1; t < f->k && coalescent; ++t)
     coalescent = X[t] == X[0] + (int64_t)t * F && Y[t] == Y[0] + (int64_t)t * F;
@@ -723,7 +942,8 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   // doubles the number of slices.
   int max_cols = 64;
   if (options().slice_cols > 0) max_cols = (int)std::min<int64_t>(64, options().slice_cols);
-  else if ((int64_t)f->k * ((F + 63) / 64) < 8 && F > 32) max_cols = 32;
+  else if ((int64_t)f->k * ((F + 63) / 64) < 8 && F > 32 && !fused) max_cols = 32;
+  if (fused) max_cols = 64;
   const int cols = std::min(F, max_cols);
   if (!coalescent) {
     a.ls_log2 = ceil_log2((cols + vec - 1) / vec);
@@ -778,7 +998,14 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   if (coalescent)
     return cvec == 4 ? launch_coalescent<4>(a, st)
                      : cvec == 2 ? launch_coalescent<2>(a, st) : launch_coalescent<1>(a, st);
-  return vec4 ? launch<4>(a, st) : launch<1>(a, st);
+  if (fused) return launch<4>(a, st, true);
+  const int rc = vec4 ? launch<4>(a, st) : launch<1>(a, st);
+  if (rc != PIPAD_OK || !upd) return rc;
+  const int64_t tiles = ((int64_t)f->n + 15) / 16 * f->k;
+  hipLaunchKernelGGL(k_update, dim3((unsigned)((tiles + kWavesPerBlock - 1) / kWavesPerBlock)),
+                     dim3(kBlock), 0, st, a);
+  PIPAD_HIP(hipGetLastError());
+  return PIPAD_OK;
 }
 
 }  // namespace pipad

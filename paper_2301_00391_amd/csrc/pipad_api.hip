@@ -98,6 +98,30 @@ int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *co
                                  static_cast<hipStream_t>(stream));
 }
 
+int pipad_frame_aggregate_update(const pipad_frame_t *frame, int32_t F, const float *const *X,
+                                 int64_t ldx, const float *W, int64_t ldw, const float *bias,
+                                 int32_t Fo, float *const *A, int64_t lda, float *const *H,
+                                 int64_t ldh, void *stream) {
+  if (!frame || !X || !H || !W || F < 1 || Fo < 1 || ldx < F || ldw < Fo || ldh < Fo)
+    return PIPAD_ERR_INVALID_ARG;
+  if (A && lda < F) return PIPAD_ERR_INVALID_ARG;
+  if (frame->n > 0)
+    for (int t = 0; t < frame->k; ++t)
+      if (!X[t] || !H[t] || (A && !A[t])) return PIPAD_ERR_INVALID_ARG;
+  const int64_t lim = (int64_t)1 << 40;
+  if ((int64_t)frame->n * ldx >= lim || (int64_t)frame->n * ldh >= lim ||
+      (A && (int64_t)frame->n * lda >= lim))
+    return PIPAD_ERR_TOO_LARGE;
+  if (frame->n > 0) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return pipad::hip_fail(hipGetLastError(), "hipGetDevice");
+    if (dev != frame->device) return PIPAD_ERR_INVALID_ARG;
+  }
+  pipad::UpdateSpec u{W, ldw, bias, Fo, H, ldh};
+  return pipad::aggregate_launch(const_cast<pipad_frame *>(frame), F, X, ldx, A, A ? lda : F,
+                                 static_cast<hipStream_t>(stream), &u);
+}
+
 void pipad_frame_destroy(pipad_frame_t *frame) { pipad::destroy_frame(frame); }
 
 const char *pipad_strerror(int status) {

@@ -81,8 +81,19 @@ struct pipad_frame {
 };
 
 namespace pipad {
+// The update that may follow the aggregation: H_t = Y_t W + bias.
+struct UpdateSpec {
+  const float *W;     // [F][Fo], row stride ldw
+  int64_t ldw;
+  const float *bias;  // [Fo] or null
+  int32_t Fo;
+  float *const *H;    // k device pointers, row stride ldh
+  int64_t ldh;
+};
+// Y may be null when `update` is given and the shape allows the fused kernel.
 int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t ldx,
-                     float *const *Y, int64_t ldy, hipStream_t stream);
+                     float *const *Y, int64_t ldy, hipStream_t stream,
+                     const UpdateSpec *update = nullptr);
 }
 
 #endif  // PIPAD_INTERNAL_H_

@@ -410,3 +410,89 @@ def test_medium_frame_full_check(pipad):
     lists = [(s.rowptr[t], s.col[t]) for t in range(cfg.k)]
     worst = run_case(pipad, cfg.n, lists, cfg.feat, cfg.seed, layout="wide", validate=False)
     print(f"medium worst error ratio {worst:.3e} of the 1e-5 budget")
+
+
+# ---- aggregation followed by the fully connected update (one GCN layer, Eq. 1) ------------------
+def update_tolerance(F):
+    """Per-element budget relative to B2 = (|A^||X|)|W| + |bias|: the aggregation's 1e-5, plus one
+    float32 rounding per term of the F-term dot product and one for the bias (unit roundoff 2^-24)."""
+    return 1e-5 + (F + 2) * 2.0 ** -24
+
+
+def run_update_case(pipad, n, lists, F, Fo, seed, with_bias=True, with_a=True, x_stride=None):
+    k = len(lists)
+    dev = "cuda:0"
+    rng = np.random.default_rng(seed)
+    snaps = [(torch.from_numpy(np.ascontiguousarray(rp)).to(dev),
+              torch.from_numpy(np.ascontiguousarray(c)).to(dev)) for rp, c in lists]
+    frame = pipad.frame_build_overlap(snaps)
+    X = [synth.features(seed, t, n, F) for t in range(k)]
+    W = (rng.standard_normal((F, Fo)) / np.sqrt(F)).astype(np.float32)
+    b = rng.standard_normal(Fo).astype(np.float32) if with_bias else None
+    xs = []
+    for x in X:
+        buf = torch.zeros((n, x_stride or F), dtype=torch.float32, device=dev)
+        buf[:, :F] = torch.from_numpy(x).to(dev)
+        xs.append(buf[:, :F])
+    A = [torch.full((n, F), float("nan"), device=dev) for _ in range(k)] if with_a else None
+    H = [torch.full((n, Fo), float("nan"), device=dev) for _ in range(k)]
+    pipad.frame_aggregate_update(frame, xs, torch.from_numpy(W).to(dev),
+                                 torch.from_numpy(b).to(dev) if with_bias else None, H=H, A=A)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for t in range(k):
+        rows, cols = csr_to_coo(n, *lists[t])
+        Hd, B2 = oracle.aggregate_update(n, rows, cols, X[t], W, b, threads=4)
+        err = np.abs(H[t].cpu().numpy().astype(np.float64) - Hd)
+        ratio = float(np.max(err / np.maximum(B2, 1e-300)))
+        assert ratio <= update_tolerance(F), f"H, snapshot {t}: {ratio:.3e}"
+        worst = max(worst, ratio)
+        if with_a:
+            _, yd, bound, _ = oracle.aggregate(n, rows, cols, X[t], threads=4)
+            check_y(A[t].cpu().numpy(), yd, bound, f"A, snapshot {t}")
+    frame.close()
+    return worst
+
+
+@pytest.mark.parametrize("k,F,Fo", [(4, 64, 64), (8, 32, 16), (3, 16, 48), (2, 48, 32), (5, 64, 16),
+                                    (1, 64, 64)])
+@pytest.mark.parametrize("with_bias,with_a", [(True, True), (False, False)])
+def test_update_fused_into_the_aggregation(pipad, k, F, Fo, with_bias, with_a):
+    rng = np.random.default_rng(40 + k + F + Fo)
+    n = 1111  # many 16-row tiles per wave and a ragged last one
+    lists = churned(rng, n, k, 0.02, 0.8)
+    run_update_case(pipad, n, lists, F, Fo, seed=k + F, with_bias=with_bias, with_a=with_a)
+
+
+def test_update_fused_with_long_and_hub_rows_and_padded_input_rows(pipad):
+    pipad.set_option("short_max", 3)
+    pipad.set_option("hub_threshold", 9)
+    pipad.set_option("hub_segment", 4)
+    rng = np.random.default_rng(4)
+    n = 700
+    lists = churned(rng, n, 4, 0.03, 0.7)
+    run_update_case(pipad, n, lists, 64, 32, seed=1, x_stride=96)
+    run_update_case(pipad, n, lists, 32, 64, seed=2, with_a=False)
+
+
+@pytest.mark.parametrize("k,F,Fo", [(2, 128, 64), (3, 20, 10), (2, 64, 80), (1, 6, 3), (2, 8, 16),
+                                    (2, 260, 33)])
+def test_update_as_a_second_step_for_other_shapes(pipad, k, F, Fo):
+    rng = np.random.default_rng(60 + k + F + Fo)
+    n = 530
+    lists = churned(rng, n, k, 0.03, 0.8)
+    run_update_case(pipad, n, lists, F, Fo, seed=F + Fo)
+
+
+def test_update_without_workspace_is_refused_for_shapes_that_need_it(pipad):
+    rng = np.random.default_rng(8)
+    n = 100
+    lists = churned(rng, n, 2, 0.05, 0.8)
+    dev = "cuda:0"
+    snaps = [(torch.from_numpy(rp).to(dev), torch.from_numpy(c).to(dev)) for rp, c in lists]
+    frame = pipad.frame_build_overlap(snaps)
+    xs = [torch.zeros((n, 128), device=dev) for _ in range(2)]
+    with pytest.raises(pipad.PipadError) as e:
+        pipad.frame_aggregate_update(frame, xs, torch.zeros((128, 16), device=dev))
+    assert e.value.status == -1
+    frame.close()
