@@ -496,3 +496,33 @@ def test_update_without_workspace_is_refused_for_shapes_that_need_it(pipad):
         pipad.frame_aggregate_update(frame, xs, torch.zeros((128, 16), device=dev))
     assert e.value.status == -1
     frame.close()
+
+
+def test_symmetric_frames_take_their_backward_pass_through_the_same_entry_point(pipad):
+    """For symmetric patterns A^_t is symmetric, so the gradient of the layer H_t = (A^_t X_t) W
+    with respect to X_t is A^_t (G_t W^T) = (A^_t G_t) W^T: the same call with W transposed.
+    Checked through the adjoint identity <H(X), G> = <X, dX(G)> and against the oracle."""
+    rng = np.random.default_rng(17)
+    n, k, F, Fo = 640, 3, 32, 48
+    lists = churned(rng, n, k, 0.02, 0.8, symmetric=True)
+    dev = "cuda:0"
+    snaps = [(torch.from_numpy(rp).to(dev), torch.from_numpy(c).to(dev)) for rp, c in lists]
+    frame = pipad.frame_build_overlap(snaps)
+    X = [synth.features(1, t, n, F) for t in range(k)]
+    G = [synth.features(2, t, n, Fo) for t in range(k)]
+    W = (rng.standard_normal((F, Fo)) / np.sqrt(F)).astype(np.float32)
+    Wd = torch.from_numpy(W).to(dev)
+    H = pipad.frame_aggregate_update(frame, [torch.from_numpy(x).to(dev) for x in X], Wd)
+    dX = pipad.frame_aggregate_update(frame, [torch.from_numpy(g).to(dev) for g in G],
+                                      Wd.t().contiguous())
+    torch.cuda.synchronize()
+    for t in range(k):
+        rows, cols = csr_to_coo(n, *lists[t])
+        dXd, B2 = oracle.aggregate_update(n, rows, cols, G[t], np.ascontiguousarray(W.T))
+        err = np.abs(dX[t].cpu().numpy().astype(np.float64) - dXd)
+        assert float(np.max(err / np.maximum(B2, 1e-300))) <= update_tolerance(Fo)
+        lhs = float(np.sum(H[t].cpu().numpy().astype(np.float64) * G[t]))
+        rhs = float(np.sum(X[t].astype(np.float64) * dX[t].cpu().numpy()))
+        scale = float(np.sum(np.abs(X[t].astype(np.float64)) * B2))
+        assert abs(lhs - rhs) <= 2 * update_tolerance(max(F, Fo)) * scale
+    frame.close()
