@@ -278,9 +278,6 @@ __device__ inline void sink_flush_ks(const AggArgs &a, const Slice &s, Sink &k, 
     const float4 v = *reinterpret_cast<const float4 *>(k.tile + m * kTileStride + g * KS + 4 * q);
     av[4 * q + 0] = v.x; av[4 * q + 1] = v.y; av[4 * q + 2] = v.z; av[4 * q + 3] = v.w;
   }
-  int32_t row[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) row[r] = k.rows[min(4 * g + r, kTileRows - 1)];
   const int ws = a.Fo + 1;
   for (int nt = 0; nt < a.Fo / 16; ++nt) {
     const float *wcol = k.wl + (g * KS) * ws + 16 * nt + m;
@@ -291,9 +288,19 @@ __device__ inline void sink_flush_ks(const AggArgs &a, const Slice &s, Sink &k, 
     mfma_f4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) d = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ks], bv[ks], d, 0, 0, 0);
+    // the A values are in registers by now: the tile takes the result rows, to leave as whole rows
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-      if (4 * g + r < k.cnt) s.ht[(int64_t)row[r] * a.ldh + 16 * nt + m] = d[r] + b;
+    for (int r = 0; r < 4; ++r) k.tile[(4 * g + r) * kTileStride + 16 * nt + m] = d[r] + b;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  // 16 rows x Fo columns leave in 16-byte pieces: lane -> (row, piece), Fo / 4 pieces per row
+  const int pieces = a.Fo >> 2;
+  for (int idx = lane; idx < kTileRows * pieces; idx += kWave) {
+    const int rr = idx / pieces, pc = idx - rr * pieces;
+    if (rr < k.cnt) {
+      const float4 v = *reinterpret_cast<const float4 *>(k.tile + rr * kTileStride + 4 * pc);
+      *reinterpret_cast<float4 *>(s.ht + (int64_t)k.rows[rr] * a.ldh + 4 * pc) = v;
+    }
   }
 }
 
@@ -909,7 +916,10 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     a.ldh = upd->ldh;
     for (int t = 0; t < f->k; ++t) a.H[t] = upd->H[t];
     fused = vec4 && F >= 16 && F <= 64 && upd->Fo >= 16 && upd->Fo <= 64 && upd->Fo % 16 == 0 &&
-            (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32) && !options().agg_generic;
+            upd->ldh % 4 == 0 && (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32) &&
+            !options().agg_generic;
+    for (int t = 0; t < f->k; ++t)
+      if (reinterpret_cast<uintptr_t>(upd->H[t]) & 15u) fused = false;  // H leaves in 16-byte pieces
     if (!fused && !Y) return PIPAD_ERR_INVALID_ARG;  // the two-step form needs Y as its workspace
   }
   // Small F handed over as one concatenated operand: the coalescent kernel (snapshot groups).
