@@ -146,8 +146,8 @@ int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *co
  *   A      host array of k device pointers receiving the aggregation results (row stride lda >= F),
  *          or NULL when they are not wanted.  NULL is only possible where the update is fused
  *          into the aggregation kernel: F and Fo multiples of 4 resp. 16 with 16 <= F, Fo <= 64,
- *          16-byte aligned X, H (and A) with ldx, ldh (lda) multiples of 4, and a snapshot matrix
- *          below 4 GiB.  Other shapes run the aggregation into A and then a separate multiplication;
+ *          16-byte aligned X (and A) with ldx (lda) a multiple of 4, and a snapshot matrix below
+ *          4 GiB.  Other shapes run the aggregation into A and then a separate multiplication;
  *          without A they return PIPAD_ERR_INVALID_ARG.
  *   H      host array of k device pointers, row stride ldh >= Fo; written once per element.
  *          H, A, X, W must not overlap.

@@ -278,29 +278,27 @@ __device__ inline void sink_flush_ks(const AggArgs &a, const Slice &s, Sink &k, 
     const float4 v = *reinterpret_cast<const float4 *>(k.tile + m * kTileStride + g * KS + 4 * q);
     av[4 * q + 0] = v.x; av[4 * q + 1] = v.y; av[4 * q + 2] = v.z; av[4 * q + 3] = v.w;
   }
+  int32_t row[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) row[r] = k.rows[min(4 * g + r, kTileRows - 1)];
   const int ws = a.Fo + 1;
   for (int nt = 0; nt < a.Fo / 16; ++nt) {
     const float *wcol = k.wl + (g * KS) * ws + 16 * nt + m;
-    float bv[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) bv[ks] = wcol[ks * ws];
     const float b = k.wl[(4 * KS) * ws + 16 * nt + m];  // the bias sits behind W's last row
     mfma_f4 d = {0.f, 0.f, 0.f, 0.f};
+    constexpr int KB = KS < 8 ? KS : 8;  // operand reads issued together (more would spill)
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) d = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ks], bv[ks], d, 0, 0, 0);
-    // the A values are in registers by now: the tile takes the result rows, to leave as whole rows
+    for (int k0 = 0; k0 < KS; k0 += KB) {
+      float bv[KB];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) k.tile[(4 * g + r) * kTileStride + 16 * nt + m] = d[r] + b;
-  }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  // 16 rows x Fo columns leave in 16-byte pieces: lane -> (row, piece), Fo / 4 pieces per row
-  const int pieces = a.Fo >> 2;
-  for (int idx = lane; idx < kTileRows * pieces; idx += kWave) {
-    const int rr = idx / pieces, pc = idx - rr * pieces;
-    if (rr < k.cnt) {
-      const float4 v = *reinterpret_cast<const float4 *>(k.tile + rr * kTileStride + 4 * pc);
-      *reinterpret_cast<float4 *>(s.ht + (int64_t)k.rows[rr] * a.ldh + 4 * pc) = v;
+      for (int ks = 0; ks < KB; ++ks) bv[ks] = wcol[(k0 + ks) * ws];
+#pragma unroll
+      for (int ks = 0; ks < KB; ++ks)
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(av[k0 + ks], bv[ks], d, 0, 0, 0);
     }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (4 * g + r < k.cnt) s.ht[(int64_t)row[r] * a.ldh + 16 * nt + m] = d[r] + b;
   }
 }
 
@@ -566,7 +564,8 @@ __global__ __launch_bounds__(kBlock) void k_update(const AggArgs a) {
   const int64_t tiles = ((int64_t)a.n + 15) / 16;
   const int64_t id = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
   if (id >= tiles * a.k) return;
-  const int t = (int)(id / tiles);
+  const int t = __builtin_amdgcn_readfirstlane((int)(id / tiles));  // one snapshot per wave
+  float *ht = a.H[t];
   const int64_t row0 = (id - t * tiles) * 16;
   const int m = lane & 15, g = lane >> 4;
   const int64_t row = row0 + m;
@@ -584,7 +583,103 @@ __global__ __launch_bounds__(kBlock) void k_update(const AggArgs a) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int64_t orow = row0 + 4 * g + r;
-      if (orow < a.n && col < a.Fo) a.H[t][orow * a.ldh + col] = d[r] + bias;
+      if (orow < a.n && col < a.Fo) ht[orow * a.ldh + col] = d[r] + bias;
+    }
+  }
+}
+
+// The same multiplication with the weights resident in LDS: a workgroup copies W's rows (all K of
+// them, zero-padded to a multiple of 64) for the `cbw` output columns of its column block
+// (blockIdx.y) once and its waves then take kUpdTiles row tiles each.  A wave stages 16 rows x 64
+// columns of Y_t at a time in its LDS tile (coalesced row reads), feeds them to the MFMAs in the
+// k order of the fused kernel, and keeps the 16 x cbw results in registers across the K chunks.
+constexpr int kUpdTiles = 8;       // row tiles per wave
+constexpr int kUpdMaxCols = 128;   // output columns per column block (8 accumulator tiles)
+
+template <int NT>  // 16-column accumulator tiles a wave keeps: NT * 16 >= cbw
+__global__ __launch_bounds__(kBlock) void k_update_resident(const AggArgs a, int cbw, int kpad) {
+  extern __shared__ __align__(16) float upd_lds[];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int m = lane & 15, g = lane >> 4;
+  const int ws = cbw + 1;
+  const int col0 = blockIdx.y * cbw;
+  for (int idx = threadIdx.x; idx < kpad * cbw; idx += kBlock) {
+    const int kk = idx / cbw, o = idx - kk * cbw;
+    upd_lds[kk * ws + o] =
+        (kk < a.F && col0 + o < a.Fo) ? a.W[(int64_t)kk * a.ldw + col0 + o] : 0.f;
+  }
+  for (int o = threadIdx.x; o < cbw; o += kBlock)
+    upd_lds[kpad * ws + o] = (a.bias && col0 + o < a.Fo) ? a.bias[col0 + o] : 0.f;
+  float *tile = upd_lds + (((kpad + 1) * ws + 3) & ~3) + wave * kTileRows * kTileStride;
+  __syncthreads();
+  const int64_t tiles = ((int64_t)a.n + 15) / 16;
+  const int64_t first = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * kUpdTiles;
+  const int64_t last = min(first + kUpdTiles, tiles * a.k);
+  const int chunks = kpad / 64;
+  // 16 rows x 64 columns of Y_t, lane = column: requested one (tile, chunk) ahead, so that the
+  // loads fly while the matrix cores work on the previous piece
+  // (the snapshot index is the same for the whole wave: said so explicitly, so that the matrix
+  // pointer is fetched once per tile through the scalar unit, not per load through a vector
+  // register; out-of-range elements are read from a clamped address and zeroed afterwards, so
+  // that the 16 loads go out together instead of one per branch)
+  auto request = [&](int64_t id, int kc, float (&v)[kTileRows]) {
+    const int t = __builtin_amdgcn_readfirstlane((int)(id / tiles));
+    const float *yt = a.Y[t];
+    const int64_t row0 = (id - t * tiles) * 16;
+    const int col = kc * 64 + lane;
+    const float *src = yt + min(col, a.F - 1);
+#pragma unroll
+    for (int j = 0; j < kTileRows; ++j) v[j] = src[min(row0 + j, (int64_t)a.n - 1) * a.ldy];
+#pragma unroll
+    for (int j = 0; j < kTileRows; ++j)
+      if (!(row0 + j < a.n && col < a.F)) v[j] = 0.f;
+  };
+  float nxt[kTileRows];
+  if (first < last) request(first, 0, nxt);
+  for (int64_t id = first; id < last; ++id) {
+    const int t = __builtin_amdgcn_readfirstlane((int)(id / tiles));
+    float *ht = a.H[t];
+    const int64_t row0 = (id - t * tiles) * 16;
+    mfma_f4 d[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) d[nt] = mfma_f4{0.f, 0.f, 0.f, 0.f};
+    for (int kc = 0; kc < chunks; ++kc) {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");  // earlier readers of the tile
+#pragma unroll
+      for (int j = 0; j < kTileRows; ++j) tile[j * kTileStride + lane] = nxt[j];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      if (kc + 1 < chunks) request(id, kc + 1, nxt);
+      else if (id + 1 < last) request(id + 1, 0, nxt);
+      float av[16];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 v = *reinterpret_cast<const float4 *>(tile + m * kTileStride + g * 16 + 4 * q);
+        av[4 * q + 0] = v.x; av[4 * q + 1] = v.y; av[4 * q + 2] = v.z; av[4 * q + 3] = v.w;
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        if (16 * nt < cbw) {
+          const float *wcol = upd_lds + (kc * 64 + g * 16) * ws + 16 * nt + m;
+          float bv[16];
+#pragma unroll
+          for (int ks = 0; ks < 16; ++ks) bv[ks] = wcol[ks * ws];
+#pragma unroll
+          for (int ks = 0; ks < 16; ++ks)
+            d[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ks], bv[ks], d[nt], 0, 0, 0);
+        }
+      }
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int col = col0 + 16 * nt + m;
+      if (16 * nt < cbw && col < a.Fo) {
+        const float b = upd_lds[kpad * ws + 16 * nt + m];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int64_t orow = row0 + 4 * g + r;
+          if (orow < a.n) ht[orow * a.ldh + col] = d[nt][r] + b;
+        }
+      }
     }
   }
 }
@@ -916,10 +1011,7 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     a.ldh = upd->ldh;
     for (int t = 0; t < f->k; ++t) a.H[t] = upd->H[t];
     fused = vec4 && F >= 16 && F <= 64 && upd->Fo >= 16 && upd->Fo <= 64 && upd->Fo % 16 == 0 &&
-            upd->ldh % 4 == 0 && (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32) &&
-            !options().agg_generic;
-    for (int t = 0; t < f->k; ++t)
-      if (reinterpret_cast<uintptr_t>(upd->H[t]) & 15u) fused = false;  // H leaves in 16-byte pieces
+            (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32) && !options().agg_generic;
     if (!fused && !Y) return PIPAD_ERR_INVALID_ARG;  // the two-step form needs Y as its workspace
   }
   // Small F handed over as one concatenated operand: the coalescent kernel (snapshot groups).
@@ -1012,8 +1104,22 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   const int rc = vec4 ? launch<4>(a, st) : launch<1>(a, st);
   if (rc != PIPAD_OK || !upd) return rc;
   const int64_t tiles = ((int64_t)f->n + 15) / 16 * f->k;
-  hipLaunchKernelGGL(k_update, dim3((unsigned)((tiles + kWavesPerBlock - 1) / kWavesPerBlock)),
-                     dim3(kBlock), 0, st, a);
+  // weights resident in LDS when a column block of them fits (40 KB, tiles on top: under 64 KB), else straight from memory
+  const int kpad = (F + 63) / 64 * 64;
+  int cbw = std::min((a.Fo + 15) / 16 * 16, kUpdMaxCols);
+  while (cbw > 16 && (size_t)(kpad + 1) * (cbw + 1) * 4 > (40u << 10)) cbw -= 16;
+  const size_t w_bytes = (((size_t)(kpad + 1) * (cbw + 1) + 3) & ~(size_t)3) * 4;
+  if (w_bytes <= (40u << 10)) {
+    const size_t lds = w_bytes + (size_t)kWavesPerBlock * kTileRows * kTileStride * 4;
+    const int64_t per_block = (int64_t)kWavesPerBlock * kUpdTiles;
+    const dim3 grid((unsigned)((tiles + per_block - 1) / per_block), (unsigned)((a.Fo + cbw - 1) / cbw));
+    auto kern = cbw <= 16 ? k_update_resident<1> : cbw <= 32 ? k_update_resident<2>
+              : cbw <= 64 ? k_update_resident<4> : k_update_resident<8>;
+    hipLaunchKernelGGL(kern, grid, dim3(kBlock), lds, st, a, cbw, kpad);
+  } else {
+    hipLaunchKernelGGL(k_update, dim3((unsigned)((tiles + kWavesPerBlock - 1) / kWavesPerBlock)),
+                       dim3(kBlock), 0, st, a);
+  }
   PIPAD_HIP(hipGetLastError());
   return PIPAD_OK;
 }

@@ -476,7 +476,7 @@ def test_update_fused_with_long_and_hub_rows_and_padded_input_rows(pipad):
 
 
 @pytest.mark.parametrize("k,F,Fo", [(2, 128, 64), (3, 20, 10), (2, 64, 80), (1, 6, 3), (2, 8, 16),
-                                    (2, 260, 33)])
+                                    (2, 260, 33), (2, 128, 200), (1, 800, 8)])
 def test_update_as_a_second_step_for_other_shapes(pipad, k, F, Fo):
     rng = np.random.default_rng(60 + k + F + Fo)
     n = 530
