@@ -144,8 +144,11 @@ struct Slice {
 
 __device__ inline Slice slice_setup(const AggArgs &a, int slice, int fl, int vec) {
   Slice s;
-  const int t = slice / a.fchunks;
-  const int fc = slice - t * a.fchunks;
+  // slice -> (snapshot, column chunk), snapshot fastest: workgroup b works on slice b mod nslices
+  // and lands on XCD b mod 8, so with k a multiple of 8 all column chunks of a snapshot share an
+  // XCD, whose L2 then serves that snapshot's index and scale streams to the later chunks
+  const int fc = slice / a.k;
+  const int t = slice - fc * a.k;
   s.fcol = (fc << a.ls_log2) * vec + fl * vec;
   s.fvalid = s.fcol < a.F;
   const int col = s.fvalid ? s.fcol : 0;  // idle lanes read column 0 and never store
