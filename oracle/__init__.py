@@ -140,3 +140,30 @@ def aggregate_update(n: int, rows, cols, X: np.ndarray, W: np.ndarray,
         H = H + b64
         B2 = B2 + np.abs(b64)
     return H, B2
+
+
+def aggregate_transposed(n: int, rows, cols, X: np.ndarray):
+    """Z = (D^-1/2 (A+I) D^-1/2)^T X for one snapshot given as an edge list: what the backward pass
+    of the aggregation multiplies by (the transposed operator, needed as such only for directed
+    patterns).  D holds the row sums of A + I, exactly as in :func:`aggregate`: transposing moves the
+    entries, not the normalisation.  Written out from the definition in float64:
+    Z[j] += X[i] / sqrt(d_i d_j) for every pair (i, j) of A + I.
+
+    Returns ``(Zd float64[n, F], B float64[n, F])`` with B the same sum over absolute values."""
+    rows, cols = _i32(rows), _i32(cols)
+    if X.shape[0] != n:
+        raise ValueError("X must have n rows")
+    keep = rows != cols
+    pairs = np.unique(np.stack([rows[keep].astype(np.int64), cols[keep].astype(np.int64)], axis=1),
+                      axis=0) if keep.any() else np.zeros((0, 2), dtype=np.int64)
+    diag = np.arange(n, dtype=np.int64)
+    r = np.concatenate([pairs[:, 0], diag])
+    c = np.concatenate([pairs[:, 1], diag])
+    d = np.bincount(r, minlength=n).astype(np.float64)
+    w = 1.0 / np.sqrt(d[r] * d[c])
+    x64 = X.astype(np.float64)
+    Zd = np.zeros((n, X.shape[1]), dtype=np.float64)
+    B = np.zeros_like(Zd)
+    np.add.at(Zd, c, w[:, None] * x64[r])
+    np.add.at(B, c, w[:, None] * np.abs(x64[r]))
+    return Zd, B
