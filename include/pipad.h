@@ -158,6 +158,19 @@ int pipad_frame_aggregate_update(const pipad_frame_t *frame, int32_t F, const fl
                                  int32_t Fo, float *const *A, int64_t lda, float *const *H,
                                  int64_t ldh, void *stream);
 
+/* The frame of the transposed patterns with the same normalisation: aggregating with `*out`
+ * multiplies by the transpose of D_t^-1/2 (A_t + I) D_t^-1/2, the operator of the backward pass
+ * (Eq. 1 differentiated; D_t keeps the row sums of A_t + I of the ORIGINAL snapshots).  For
+ * symmetric patterns the result equals the input frame and the call is not needed.
+ *
+ *   frame   a frame built on the current device; not modified, may be destroyed afterwards
+ *   alloc, alloc_ctx, stream   as for pipad_frame_build_overlap (one host synchronisation)
+ *   out     receives the new frame: its common / exclusive parts are the transposes of `frame`'s
+ *           (canonical CSR again), its D^-1/2 is a copy.
+ * Errors as for pipad_frame_build_overlap; *out is untouched on failure. */
+int pipad_frame_transpose(const pipad_frame_t *frame, pipad_alloc_fn alloc, void *alloc_ctx,
+                          void *stream, pipad_frame_t **out);
+
 /* Releases the frame and every buffer the library allocated itself.  NULL is allowed. */
 void pipad_frame_destroy(pipad_frame_t *frame);
 

@@ -4,7 +4,8 @@ The compute lives in ``libpipad.so`` (sources under ``csrc/``, contract in ``inc
 this package is the thin binding.  There is no CPU fallback.
 """
 from .binding import (Frame, PipadError, frame_aggregate, frame_aggregate_update,
-                      frame_build_overlap, get_option, load_library, set_option)
+                      frame_build_overlap, frame_transpose, get_option, load_library,
+                      set_option)
 
 
 def coalescent_row_bytes(snapshots: int, feat: int) -> int:
@@ -25,5 +26,5 @@ def padded_row_stride(feat: int) -> int:
     return lines * 32
 
 
-__all__ = ["Frame", "PipadError", "frame_aggregate", "frame_aggregate_update", "frame_build_overlap", "get_option",
+__all__ = ["Frame", "PipadError", "frame_aggregate", "frame_aggregate_update", "frame_build_overlap", "frame_transpose", "get_option",
            "set_option", "load_library", "coalescent_row_bytes", "padded_row_stride"]

@@ -53,6 +53,7 @@ SIGNATURES = {
     "pipad_frame_aggregate_update": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_vp), _i64, _vp, _i64,
                                                     _vp, _i32, ctypes.POINTER(_vp), _i64,
                                                     ctypes.POINTER(_vp), _i64, _vp]),
+    "pipad_frame_transpose": (ctypes.c_int, [_vp, _vp, _vp, _vp, ctypes.POINTER(_vp)]),
     "pipad_frame_destroy": (None, [_vp]),
     "pipad_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "pipad_last_hip_error": (ctypes.c_char_p, []),
@@ -170,6 +171,37 @@ class Frame:
         return _copy_from_device(ptr.value, self.k * self.n, torch.float32, self.device).view(self.k, self.n)
 
 
+def _make_allocator(allocator: str, device):
+    """(list that keeps the handed-out tensors alive, C callback or None)."""
+    buffers: list = []
+    if allocator == "library":
+        return buffers, None
+    if allocator != "torch":
+        raise ValueError("allocator must be 'torch' or 'library'")
+
+    def _alloc(nbytes, _ctx):
+        try:
+            buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+            buffers.append(buf)
+            return buf.data_ptr()
+        except Exception:  # out of memory -> NULL -> PIPAD_ERR_ALLOC
+            return None
+    return buffers, ALLOC_FN(_alloc)
+
+
+def frame_transpose(frame: Frame, allocator: str = "torch", stream=None) -> Frame:
+    """pipad_frame_transpose: the frame of the transposed patterns with the same D^-1/2; aggregating
+    with it applies the transposed operator (the backward pass for directed patterns)."""
+    lib = load_library()
+    buffers, cb = _make_allocator(allocator, frame.device)
+    out = _vp()
+    with torch.cuda.device(frame.device):
+        status = lib.pipad_frame_transpose(frame._h, ctypes.cast(cb, _vp) if cb is not None else None,
+                                           None, _stream_handle(stream), ctypes.byref(out))
+    _check(status)
+    return Frame(out.value, frame.n, frame.k, frame.device, buffers, cb)
+
+
 def frame_build_overlap(snapshots: Sequence[Snapshot], validate: bool = False,
                         allocator: str = "torch", stream=None) -> Frame:
     """pipad_frame_build_overlap: k CSR snapshots -> frame (overlap CSR + k exclusive CSRs + D^-1/2).
@@ -194,21 +226,7 @@ def frame_build_overlap(snapshots: Sequence[Snapshot], validate: bool = False,
         arr[t].nnz = col.numel()
         arr[t].rowptr = rp.data_ptr()
         arr[t].colidx = col.data_ptr() if col.numel() else None
-    buffers: list = []
-    cb = None
-    failed = []
-    if allocator == "torch":
-        def _alloc(nbytes, _ctx):
-            try:
-                buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
-                buffers.append(buf)
-                return buf.data_ptr()
-            except Exception as exc:  # out of memory -> NULL -> PIPAD_ERR_ALLOC
-                failed.append(exc)
-                return None
-        cb = ALLOC_FN(_alloc)
-    elif allocator != "library":
-        raise ValueError("allocator must be 'torch' or 'library'")
+    buffers, cb = _make_allocator(allocator, device)
     out = _vp()
     with torch.cuda.device(device):
         status = lib.pipad_frame_build_overlap(

@@ -23,6 +23,8 @@ Options &options() {
 int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags,
                   pipad_alloc_fn alloc, void *alloc_ctx, hipStream_t st, pipad_frame **out);
 void destroy_frame(pipad_frame *f);
+int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx, hipStream_t st,
+                    pipad_frame **out);
 
 }  // namespace pipad
 
@@ -120,6 +122,19 @@ int pipad_frame_aggregate_update(const pipad_frame_t *frame, int32_t F, const fl
   pipad::UpdateSpec u{W, ldw, bias, Fo, H, ldh};
   return pipad::aggregate_launch(const_cast<pipad_frame *>(frame), F, X, ldx, A, A ? lda : F,
                                  static_cast<hipStream_t>(stream), &u);
+}
+
+int pipad_frame_transpose(const pipad_frame_t *frame, pipad_alloc_fn alloc, void *alloc_ctx,
+                          void *stream, pipad_frame_t **out) {
+  if (!frame || !out) return PIPAD_ERR_INVALID_ARG;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return pipad::hip_fail(hipGetLastError(), "hipGetDevice");
+  if (dev != frame->device) return PIPAD_ERR_INVALID_ARG;
+  pipad_frame *g = nullptr;
+  const int rc = pipad::transpose_frame(frame, alloc, alloc_ctx, static_cast<hipStream_t>(stream), &g);
+  if (rc != PIPAD_OK) return rc;
+  *out = g;
+  return PIPAD_OK;
 }
 
 void pipad_frame_destroy(pipad_frame_t *frame) { pipad::destroy_frame(frame); }

@@ -526,3 +526,66 @@ def test_symmetric_frames_take_their_backward_pass_through_the_same_entry_point(
         scale = float(np.sum(np.abs(X[t].astype(np.float64)) * B2))
         assert abs(lhs - rhs) <= 2 * update_tolerance(max(F, Fo)) * scale
     frame.close()
+
+
+# ---- transposed frames (the backward operator for directed patterns) ----------------------------
+def transpose_csr(n, rowptr, col):
+    rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))
+    order = np.lexsort((rows, col))  # by column, then by row: the transposed CSR's order
+    t_rowptr = np.concatenate([[0], np.cumsum(np.bincount(col, minlength=n))]).astype(np.int32)
+    return t_rowptr, rows[order].astype(np.int32)
+
+
+@pytest.mark.parametrize("k,n,p,keep,F,classes", [(3, 300, 0.05, 0.7, 24, None), (1, 64, 0.2, 1.0, 4, None),
+                                                  (8, 1500, 0.01, 0.9, 64, None),
+                                                  (4, 400, 0.05, 0.7, 16, (2, 8, 4))])
+def test_transposed_frame_of_directed_patterns(pipad, k, n, p, keep, F, classes):
+    if classes:
+        pipad.set_option("short_max", classes[0])
+        pipad.set_option("hub_threshold", classes[1])
+        pipad.set_option("hub_segment", classes[2])
+    rng = np.random.default_rng(1000 + k + n)
+    lists = churned(rng, n, k, p, keep, symmetric=False)
+    dev = "cuda:0"
+    snaps = [(torch.from_numpy(rp).to(dev), torch.from_numpy(c).to(dev)) for rp, c in lists]
+    frame = pipad.frame_build_overlap(snaps)
+    tframe = pipad.frame_transpose(frame)
+    # the parts: bit-exact transposes of the forward frame's parts; D^-1/2 unchanged
+    for part in [None] + list(range(k)):
+        rp, col = (frame.common() if part is None else frame.delta(part))
+        trp, tcol = (tframe.common() if part is None else tframe.delta(part))
+        want_rp, want_col = transpose_csr(n, rp.cpu().numpy(), col.cpu().numpy())
+        assert np.array_equal(trp.cpu().numpy(), want_rp), f"rowptr of part {part}"
+        assert np.array_equal(tcol.cpu().numpy(), want_col), f"columns of part {part}"
+    assert torch.equal(frame.dinv(), tframe.dinv())
+    frame.close()  # the transposed frame stands on its own
+    G = [synth.features(9, t, n, F) for t in range(k)]
+    Z = pipad.frame_aggregate(tframe, [torch.from_numpy(g).to(dev) for g in G])
+    torch.cuda.synchronize()
+    for t in range(k):
+        rows, cols = csr_to_coo(n, *lists[t])
+        Zd, B = oracle.aggregate_transposed(n, rows, cols, G[t])
+        check_y(Z[t].cpu().numpy(), Zd, B, f"transposed snapshot {t}")
+    tframe.close()
+
+
+def test_transposing_a_symmetric_frame_changes_nothing_and_library_allocator_works(pipad):
+    rng = np.random.default_rng(3)
+    n, k = 500, 3
+    lists = churned(rng, n, k, 0.03, 0.8, symmetric=True)
+    dev = "cuda:0"
+    snaps = [(torch.from_numpy(rp).to(dev), torch.from_numpy(c).to(dev)) for rp, c in lists]
+    frame = pipad.frame_build_overlap(snaps, allocator="library")
+    tframe = pipad.frame_transpose(frame, allocator="library")
+    for part in [None] + list(range(k)):
+        a = frame.common() if part is None else frame.delta(part)
+        b = tframe.common() if part is None else tframe.delta(part)
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    X = [torch.from_numpy(synth.features(4, t, n, 32)).to(dev) for t in range(k)]
+    Y1 = pipad.frame_aggregate(frame, X)
+    Y2 = pipad.frame_aggregate(tframe, X)
+    torch.cuda.synchronize()
+    for t in range(k):
+        assert torch.equal(Y1[t], Y2[t])
+    frame.close()
+    tframe.close()
