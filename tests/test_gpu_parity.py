@@ -589,3 +589,35 @@ def test_transposing_a_symmetric_frame_changes_nothing_and_library_allocator_wor
         assert torch.equal(Y1[t], Y2[t])
     frame.close()
     tframe.close()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_randomised_frames(pipad, seed):
+    """Seeded random frames over the whole parameter space of the extraction: node counts from 1 up,
+    1 to 32 snapshots, rows from empty to thousands of entries, churn from none to total, directed
+    and symmetric patterns, random row-class thresholds.  CSRs bit-exact, aggregation in tolerance."""
+    rng = np.random.default_rng(7000 + seed)
+    n = int(rng.choice([1, 2, 63, 64, 65, 200, 777, 1500, 2600]))
+    k = int(rng.choice([1, 2, 3, 5, 8, 9, 16, 17, 32]))
+    if n * n * k > 40_000_000:
+        k = max(1, 40_000_000 // (n * n))
+    symmetric = bool(rng.integers(2))
+    keep = float(rng.choice([0.0, 0.5, 0.9, 0.99, 1.0]))
+    dens = np.full((n, 1), float(rng.choice([0.0, 0.002, 0.02, 0.2])))
+    hubs = rng.choice(n, min(n, int(rng.integers(0, 4))), replace=False)
+    dens[hubs] = float(rng.choice([0.5, 0.95]))
+    base = rng.random((n, n)) < dens
+    lists = []
+    for _ in range(k):
+        M = base & (rng.random((n, n)) < keep) | (rng.random((n, n)) < dens * (1 - keep))
+        if symmetric:
+            M = np.triu(M, 1)
+            M = M | M.T
+        np.fill_diagonal(M, False)
+        rowptr = np.concatenate([[0], np.cumsum(M.sum(axis=1))]).astype(np.int32)
+        lists.append((rowptr, np.nonzero(M)[1].astype(np.int32)))
+    pipad.set_option("short_max", int(rng.choice([0, 4, 32])))
+    pipad.set_option("hub_threshold", int(rng.choice([8, 100, 2048])))
+    pipad.set_option("hub_segment", int(rng.choice([3, 64, 1024])))
+    F = int(rng.choice([1, 4, 7, 16, 64, 96]))
+    run_case(pipad, n, lists, F, seed=seed, layout="list" if seed % 2 else "wide")
