@@ -327,8 +327,9 @@ __global__ __launch_bounds__(kBlock) void k_pack(Snaps s, Parts p) {
 
 // ---- count ----------------------------------------------------------------------------------
 // grid.y = part; cnt[word_off[part] + w] = number of selected entries in word w.
-__global__ __launch_bounds__(kBlock) void k_popcount(Snaps s, Parts p, uint32_t *cnt) {
+__global__ __launch_bounds__(kBlock) void k_popcount(Snaps s, Parts p, uint32_t *cnt, uint32_t m) {
   const int part = blockIdx.y;
+  if (part == 0 && blockIdx.x == 0 && threadIdx.x == 0) cnt[m - 1] = 0;  // the trailing word
   const uint32_t nw = p.word_off[part + 1] - p.word_off[part];
   const uint32_t w = blockIdx.x * kBlock + threadIdx.x;
   if (w < nw) cnt[p.word_off[part] + w] = (uint32_t)__popcll(selected_word(p, s, part, w));
@@ -362,8 +363,15 @@ __device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t &total) {
   return before + inc - v;
 }
 
-__global__ __launch_bounds__(kBlock) void k_scan_reduce(const uint32_t *data, uint32_t m,
-                                                         uint32_t *bsum) {
+// Up to kScanBatch arrays of one length are scanned by the same three launches (grid.y = array).
+constexpr int kScanBatch = 3;
+struct ScanBatch {
+  uint32_t *data[kScanBatch];
+  uint32_t *bsum[kScanBatch];  // ceil(m / kScanTile) words each
+};
+
+__global__ __launch_bounds__(kBlock) void k_scan_reduce(ScanBatch b, uint32_t m) {
+  const uint32_t *data = b.data[blockIdx.y];
   const uint32_t base = blockIdx.x * (uint32_t)kScanTile + threadIdx.x * kScanItems;
   uint32_t s = 0;
 #pragma unroll
@@ -371,10 +379,11 @@ __global__ __launch_bounds__(kBlock) void k_scan_reduce(const uint32_t *data, ui
     if (base + q < m) s += data[base + q];
   uint32_t total;
   block_exclusive_scan(s, total);
-  if (threadIdx.x == 0) bsum[blockIdx.x] = total;
+  if (threadIdx.x == 0) b.bsum[blockIdx.y][blockIdx.x] = total;
 }
 
-__global__ __launch_bounds__(kBlock) void k_scan_blocksums(uint32_t *bsum, uint32_t nb) {
+__global__ __launch_bounds__(kBlock) void k_scan_blocksums(ScanBatch b, uint32_t nb) {
+  uint32_t *bsum = b.bsum[blockIdx.x];
   uint32_t carry = 0;
   for (uint32_t base = 0; base < nb; base += kBlock) {
     const uint32_t idx = base + threadIdx.x;
@@ -386,8 +395,8 @@ __global__ __launch_bounds__(kBlock) void k_scan_blocksums(uint32_t *bsum, uint3
   }
 }
 
-__global__ __launch_bounds__(kBlock) void k_scan_apply(uint32_t *data, uint32_t m,
-                                                        const uint32_t *bsum) {
+__global__ __launch_bounds__(kBlock) void k_scan_apply(ScanBatch b, uint32_t m) {
+  uint32_t *data = b.data[blockIdx.y];
   const uint32_t base = blockIdx.x * (uint32_t)kScanTile + threadIdx.x * kScanItems;
   uint32_t v[kScanItems];
   uint32_t s = 0;
@@ -397,7 +406,7 @@ __global__ __launch_bounds__(kBlock) void k_scan_apply(uint32_t *data, uint32_t 
     s += v[q];
   }
   uint32_t total;
-  uint32_t pre = block_exclusive_scan(s, total) + bsum[blockIdx.x];
+  uint32_t pre = block_exclusive_scan(s, total) + b.bsum[blockIdx.y][blockIdx.x];
 #pragma unroll
   for (int q = 0; q < kScanItems; ++q) {
     if (base + q < m) data[base + q] = pre;
@@ -405,15 +414,25 @@ __global__ __launch_bounds__(kBlock) void k_scan_apply(uint32_t *data, uint32_t 
   }
 }
 
-// In-place exclusive scan of data[0..m); bsum must hold ceil(m / kScanTile) words.
-int exclusive_scan(uint32_t *data, uint32_t m, uint32_t *bsum, hipStream_t st) {
-  if (m == 0) return PIPAD_OK;
+// In-place exclusive scans of `count` arrays data[j][0..m); bsum holds count * ceil(m / kScanTile)
+// words.
+int exclusive_scan(uint32_t *const *data, int count, uint32_t m, uint32_t *bsum, hipStream_t st) {
+  if (m == 0 || count == 0) return PIPAD_OK;
   const uint32_t nb = (m + kScanTile - 1) / kScanTile;
-  hipLaunchKernelGGL(k_scan_reduce, dim3(nb), dim3(kBlock), 0, st, data, m, bsum);
-  hipLaunchKernelGGL(k_scan_blocksums, dim3(1), dim3(kBlock), 0, st, bsum, nb);
-  hipLaunchKernelGGL(k_scan_apply, dim3(nb), dim3(kBlock), 0, st, data, m, bsum);
+  ScanBatch b;
+  for (int j = 0; j < kScanBatch; ++j) {
+    b.data[j] = data[j < count ? j : 0];
+    b.bsum[j] = bsum + (size_t)(j < count ? j : 0) * nb;
+  }
+  hipLaunchKernelGGL(k_scan_reduce, dim3(nb, count), dim3(kBlock), 0, st, b, m);
+  hipLaunchKernelGGL(k_scan_blocksums, dim3(count), dim3(kBlock), 0, st, b, nb);
+  hipLaunchKernelGGL(k_scan_apply, dim3(nb, count), dim3(kBlock), 0, st, b, m);
   PIPAD_HIP(hipGetLastError());
   return PIPAD_OK;
+}
+
+int exclusive_scan(uint32_t *data, uint32_t m, uint32_t *bsum, hipStream_t st) {
+  return exclusive_scan(&data, 1, m, bsum, st);
 }
 
 // ---- row pointers of every part ---------------------------------------------------------------
@@ -716,7 +735,8 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   float *dinv_nk = nullptr;
   int *dflags = nullptr;
   tmp.want(&pre, (size_t)m);
-  tmp.want(&bsum, (std::max<size_t>(m, scan_len_rows) + kScanTile - 1) / kScanTile + 1);
+  tmp.want(&bsum, std::max(((size_t)m + kScanTile - 1) / kScanTile,
+                           3 * (((size_t)scan_len_rows + kScanTile - 1) / kScanTile)) + 1);
   tmp.want(&shortidx, (size_t)scan_len_rows);
   tmp.want(&hubidx, (size_t)scan_len_rows);
   tmp.want(&segoff, (size_t)scan_len_rows);
@@ -742,10 +762,9 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   } while (0)
 
   if (flag_bytes) PIPAD_TRY(hipMemsetAsync(temp, 0, flag_bytes, st));
-  PIPAD_TRY(hipMemsetAsync(dflags, 0, 256, st));
-  PIPAD_TRY(hipMemsetAsync(pre + (m - 1), 0, 4, st));  // trailing word
 
   if ((flags & PIPAD_VALIDATE) && n > 0) {
+    PIPAD_TRY(hipMemsetAsync(dflags, 0, 256, st));
     hipLaunchKernelGGL(k_validate, grid1((int64_t)k * n, kWavesPerBlock), dim3(kBlock), 0, st, s, n,
                        k, dflags);
     int bad = 0;
@@ -772,7 +791,9 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   uint32_t max_nw = 0;
   for (int t = 0; t < k; ++t) max_nw = std::max(max_nw, nw[t]);
   if (max_nw > 0)
-    hipLaunchKernelGGL(k_popcount, grid1(max_nw, kBlock, k + 1), dim3(kBlock), 0, st, s, p, pre);
+    hipLaunchKernelGGL(k_popcount, grid1(max_nw, kBlock, k + 1), dim3(kBlock), 0, st, s, p, pre, m);
+  else
+    PIPAD_TRY(hipMemsetAsync(pre, 0, sizeof(uint32_t) * (size_t)m, st));  // no entries at all
   PIPAD_TRY(hipGetLastError());
   {
     int rc = exclusive_scan(pre, m, bsum, st);
@@ -785,9 +806,8 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
                      f->hub_segment);
   PIPAD_TRY(hipGetLastError());
   {
-    int rc = exclusive_scan(shortidx, scan_len_rows, bsum, st);
-    if (rc == 0) rc = exclusive_scan(hubidx, scan_len_rows, bsum, st);
-    if (rc == 0) rc = exclusive_scan(segoff, scan_len_rows, bsum, st);
+    uint32_t *three[3] = {shortidx, hubidx, segoff};
+    const int rc = exclusive_scan(three, 3, scan_len_rows, bsum, st);
     if (rc != 0) return fail(rc);
   }
 
@@ -1007,7 +1027,7 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
   tmp.want(&rows, (size_t)max_nnz);
   tmp.want(&sorted, (size_t)max_nnz);
   tmp.want(&sort_tmp, sort_bytes);
-  tmp.want(&bsum, ((size_t)scan_len + kScanTile - 1) / kScanTile + 1);
+  tmp.want(&bsum, 3 * (((size_t)scan_len + kScanTile - 1) / kScanTile) + 1);
   tmp.want(&shortidx, (size_t)scan_len);
   tmp.want(&hubidx, (size_t)scan_len);
   tmp.want(&segoff, (size_t)scan_len);
@@ -1055,9 +1075,8 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
                      hubidx, segoff, g->short_max, g->hub_threshold, g->hub_segment);
   PIPAD_TRY_T(hipGetLastError());
   {
-    int rc = exclusive_scan(shortidx, scan_len, bsum, st);
-    if (rc == 0) rc = exclusive_scan(hubidx, scan_len, bsum, st);
-    if (rc == 0) rc = exclusive_scan(segoff, scan_len, bsum, st);
+    uint32_t *three[3] = {shortidx, hubidx, segoff};
+    const int rc = exclusive_scan(three, 3, scan_len, bsum, st);
     if (rc != 0) return fail(rc);
   }
   uint32_t host_totals[3] = {0, 0, 0};
