@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpipad.so")
-SOURCES = ["pipad_api.hip", "pipad_build.hip", "pipad_aggregate.hip"]
+SOURCES = ["pipad_api.hip", "pipad_build.hip", "pipad_aggregate.hip", "pipad_transpose.hip"]
 
 
 def hipcc() -> str:

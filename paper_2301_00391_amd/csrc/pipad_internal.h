@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstddef>
 #include <cstdint>
 #include <vector>
@@ -81,6 +82,65 @@ struct pipad_frame {
 };
 
 namespace pipad {
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Sub-allocates many arrays from one allocation: first every array registers its size, then
+// assign() hands out 256-byte aligned pieces of the block.
+struct Arena {
+  struct Want { void **slot; size_t offset; };
+  std::vector<Want> wants;
+  size_t total = 0;
+  template <class T> void want(T **slot, size_t count) {
+    wants.push_back({reinterpret_cast<void **>(slot), total});
+    total += align_up(std::max<size_t>(count * sizeof(T), 1), 256);
+  }
+  void assign(void *base) {
+    for (const Want &w : wants) *w.slot = static_cast<char *>(base) + w.offset;
+  }
+};
+
+struct Allocator {
+  pipad_alloc_fn fn;
+  void *ctx;
+  pipad_frame *frame;
+  // Returns nullptr on failure.  bytes == 0 still returns a valid (tiny) buffer.
+  void *get(size_t bytes) {
+    bytes = std::max<size_t>(bytes, 256);
+    void *ptr = nullptr;
+    if (fn) {
+      ptr = fn(bytes, ctx);
+    } else {
+      if (hipMalloc(&ptr, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        ptr = nullptr;
+      }
+      if (ptr) frame->owned.push_back(ptr);
+    }
+    return ptr;
+  }
+};
+
+inline void release(pipad_frame *f) {
+  if (!f) return;
+  if (f->own_memory)
+    for (void *ptr : f->owned) (void)hipFree(ptr);
+  if (f->partial && f->own_memory) (void)hipFree(f->partial);
+  delete f;
+}
+
+inline dim3 grid1(int64_t items, int per_block, int y = 1) {
+  return dim3((unsigned)((items + per_block - 1) / per_block), (unsigned)y);
+}
+
+
+// Helpers of the build that the transposition shares (defined in pipad_build.hip).
+// In-place exclusive scans of `count` (<= 3) arrays of m words; bsum: count * scan_block_words(m).
+int scan_exclusive(uint32_t *const *data, int count, uint32_t m, uint32_t *bsum, hipStream_t st);
+size_t scan_block_words(uint32_t m);
+// Fills the frame's row lists from the scanned class flags (n + 1 words each).
+void launch_row_lists(int32_t n, const uint32_t *shortidx, const uint32_t *hubidx,
+                      const uint32_t *segoff, pipad_frame *f, hipStream_t st);
+
 // The update that may follow the aggregation: H_t = Y_t W + bias.
 struct UpdateSpec {
   const float *W;     // [F][Fo], row stride ldw
