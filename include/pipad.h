@@ -190,7 +190,11 @@ const char *pipad_last_hip_error(void);
  *   "agg_nt"         bit 0: non-temporal stores for Y; bit 1: non-temporal loads for the index and
  *                    scale streams (default 0)
  *   "slice_cols"     feature columns per slice, at most 64 (default 0: 64, or 32 when that is needed
- *                    to have at least 8 slices)
+ *                    to have at least 8 slices or "agg_order" asks for it)
+ *   "agg_order"      order of the slices in time: 0 all snapshots side by side (one per XCD),
+ *                    1 one snapshot after the other (the whole chip on one matrix, 32-column
+ *                    slices), 2 automatic (default): 1 for matrices of 64 MB and more per snapshot
+ *                    or more than 64 columns
  *   "agg_generic"    1 forces the bounds-checked kernel with 64-bit addresses (default 0: only for
  *                    matrices of 4 GB and more)
  *   "agg_coalescent" kernel for F < 32 on the concatenated operand that gathers the rows of

@@ -161,6 +161,7 @@ static int64_t *option_slot(const char *key) {
   if (!std::strcmp(key, "agg_parts")) return &o.agg_parts;
   if (!std::strcmp(key, "agg_generic")) return &o.agg_generic;
   if (!std::strcmp(key, "slice_cols")) return &o.slice_cols;
+  if (!std::strcmp(key, "agg_order")) return &o.agg_order;
   if (!std::strcmp(key, "agg_coalescent")) return &o.agg_coalescent;
   if (!std::strcmp(key, "hub_threshold")) return &o.hub_threshold;
   if (!std::strcmp(key, "hub_segment")) return &o.hub_segment;

@@ -34,6 +34,7 @@ struct Options {
   int64_t agg_coalescent = 1;   // small-F coalescent kernel: 0 never, 1 automatic, 2 whenever possible
   int64_t slice_cols = 0;       // columns per slice (0: automatic, else at most 64)
   int64_t agg_generic = 0;      // 1: force the generic (bounds-checked, 64-bit address) kernel
+  int64_t agg_order = 2;        // 0: all snapshots' slices side by side, 1: one snapshot after the other, 2: automatic
   int64_t agg_parts = 7;        // timing only: bit 0 hub segments, bit 1 long rows, bit 2 short rows
 };
 Options &options();

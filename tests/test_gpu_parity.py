@@ -13,7 +13,7 @@ from _util import check_overlap, check_y, csr_to_coo, to_gpu_snapshots
 pytestmark = pytest.mark.gpu
 
 DEFAULT_OPTIONS = {"short_max": 32, "hub_threshold": 2048, "hub_segment": 1024, "agg_nt": 0,
-                   "agg_parts": 7, "agg_generic": 0, "agg_coalescent": 1, "slice_cols": 0}
+                   "agg_parts": 7, "agg_generic": 0, "agg_coalescent": 1, "slice_cols": 0, "agg_order": 2}
 
 torch = pytest.importorskip("torch")
 
@@ -89,11 +89,12 @@ def churned(rng, n, k, p, keep, symmetric=True):
     return out
 
 
-@pytest.mark.parametrize("nt,coalescent", [(0, 1), (3, 2)])
+@pytest.mark.parametrize("nt,coalescent,order", [(0, 1, 0), (3, 2, 1)])
 @pytest.mark.parametrize("layout", ["list", "wide"])
-def test_tiny_config(pipad, nt, coalescent, layout):
+def test_tiny_config(pipad, nt, coalescent, order, layout):
     pipad.set_option("agg_nt", nt)
     pipad.set_option("agg_coalescent", coalescent)
+    pipad.set_option("agg_order", order)
     cfg = synth.CONFIGS["tiny"]
     s = synth.make(cfg)
     lists = [(s.rowptr[t], s.col[t]) for t in range(cfg.k)]
@@ -110,10 +111,11 @@ def test_small_config_sliding_frames(pipad, first):
 
 @pytest.mark.parametrize("k,F", [(1, 1), (2, 2), (3, 6), (4, 16), (5, 20), (8, 64), (8, 128),
                                  (2, 130), (16, 32), (3, 260), (32, 4), (8, 256), (7, 12)])
-@pytest.mark.parametrize("short_max,generic", [(32, 0), (4, 0), (4, 1)])
-def test_shapes_and_feature_widths(pipad, k, F, short_max, generic):
+@pytest.mark.parametrize("short_max,generic,order", [(32, 0, 0), (4, 0, 1), (4, 1, 1), (32, 0, 1)])
+def test_shapes_and_feature_widths(pipad, k, F, short_max, generic, order):
     pipad.set_option("short_max", short_max)
     pipad.set_option("agg_generic", generic)
+    pipad.set_option("agg_order", order)
     rng = np.random.default_rng(1000 * k + F)
     n = 333  # several workgroups and a ragged tail
     lists = churned(rng, n, k, 0.03, 0.8)
@@ -130,6 +132,10 @@ def test_row_classes_short_long_hub(pipad, short_max, threshold, segment):
     rng = np.random.default_rng(77)
     n = 500
     lists = churned(rng, n, 4, 0.04, 0.7)
+    pipad.set_option("agg_order", 1)
+    run_case(pipad, n, lists, 130, seed=4)
+    run_case(pipad, n, lists, 64, seed=4, layout="wide")
+    pipad.set_option("agg_order", 0)
     run_case(pipad, n, lists, 16, seed=5)
     run_case(pipad, n, lists, 9, seed=6)
     run_case(pipad, n, lists, 64, seed=7, layout="wide")
@@ -465,6 +471,7 @@ def test_update_fused_into_the_aggregation(pipad, k, F, Fo, with_bias, with_a):
 
 
 def test_update_fused_with_long_and_hub_rows_and_padded_input_rows(pipad):
+    pipad.set_option("agg_order", 1)
     pipad.set_option("short_max", 3)
     pipad.set_option("hub_threshold", 9)
     pipad.set_option("hub_segment", 4)
@@ -619,5 +626,6 @@ def test_randomised_frames(pipad, seed):
     pipad.set_option("short_max", int(rng.choice([0, 4, 32])))
     pipad.set_option("hub_threshold", int(rng.choice([8, 100, 2048])))
     pipad.set_option("hub_segment", int(rng.choice([3, 64, 1024])))
+    pipad.set_option("agg_order", int(rng.integers(3)))
     F = int(rng.choice([1, 4, 7, 16, 64, 96]))
     run_case(pipad, n, lists, F, seed=seed, layout="list" if seed % 2 else "wide")
