@@ -8,6 +8,7 @@ on the synthetic generator instead of the paper's datasets.
   python -m paper_2301_00391_amd.sweeps overlap   # churn x k table
   python -m paper_2301_00391_amd.sweeps features  # F x k table
   python -m paper_2301_00391_amd.sweeps sliding   # cost per new snapshot when the frame slides by one
+  python -m paper_2301_00391_amd.sweeps workloads # the benchmark frames: one frame vs one snapshot at a time
 
 Every cell times ``pipad_frame_aggregate`` of one frame of k snapshots and, as the baseline, the
 same k snapshots aggregated one at a time (k frames of a single snapshot each, whose overlap part
@@ -142,6 +143,44 @@ def sliding_sweep(dev):
               f"{t_enter:.3f} | {t_group:.3f} |", flush=True)
 
 
+def workload_sweep(dev):
+    """The benchmark workloads in the benchmark layout: one frame of k snapshots against the same
+    snapshots handled one at a time (k frames of one snapshot, whose overlap part is the whole
+    snapshot), for the extraction and for the aggregation."""
+    print("ms per frame; aggregation in the benchmark layout (rows of X padded to an odd number of "
+          "128-byte lines)\n")
+    print("| workload | extraction: frame | extraction: k single snapshots | aggregation: frame | "
+          "aggregation: one at a time |")
+    print("|---|---|---|---|---|")
+    for name in ("medium", "large", "low-overlap"):
+        cfg = synth.CONFIGS[name]
+        n, k, feat = cfg.n, cfg.k, cfg.feat
+        snaps = synth.graphs(n, cfg.edges, k, cfg.churn, cfg.model, cfg.params, cfg.seed)
+        gs = [(torch.from_numpy(snaps.rowptr[t]).to(dev), torch.from_numpy(snaps.col[t]).to(dev))
+              for t in range(k)]
+        stride = pipad.padded_row_stride(feat)
+        xb = [torch.rand((n, stride), device=dev) * 2 - 1 for _ in range(k)]
+        xs = [b[:, :feat] for b in xb]
+        ys = [torch.empty((n, feat), device=dev) for _ in range(k)]
+        frame = pipad.frame_build_overlap(gs)
+        singles = [pipad.frame_build_overlap([g]) for g in gs]
+
+        def one_by_one():
+            for t in range(k):
+                pipad.frame_aggregate(singles[t], [xs[t]], [ys[t]])
+
+        t_frame = _time(lambda: pipad.frame_aggregate(frame, xs, ys))
+        t_single = _time(one_by_one)
+        b_frame = _time(lambda: pipad.frame_build_overlap(gs), 3)
+        b_single = _time(lambda: [pipad.frame_build_overlap([g]) for g in gs], 3)
+        print(f"| {name} (N = {n}, k = {k}, F = {feat}) | {b_frame:.2f} | {b_single:.2f} | "
+              f"{t_frame:.3f} | {t_single:.3f} |", flush=True)
+        for f in singles:
+            f.close()
+        frame.close()
+        del xb, xs, ys, gs
+
+
 def main(argv):
     if not torch.cuda.is_available():
         print("sweeps need a GPU", file=sys.stderr)
@@ -154,6 +193,8 @@ def main(argv):
         feature_sweep(dev)
     elif which == "sliding":
         sliding_sweep(dev)
+    elif which == "workloads":
+        workload_sweep(dev)
     else:
         print(__doc__, file=sys.stderr)
         return 2
