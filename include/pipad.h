@@ -198,8 +198,9 @@ const char *pipad_last_hip_error(void);
  *   "agg_generic"    1 forces the bounds-checked kernel with 64-bit addresses (default 0: only for
  *                    matrices of 4 GB and more)
  *   "agg_coalescent" kernel for F < 32 on the concatenated operand that gathers the rows of
- *                    several snapshots with one access: 0 never, 1 automatic (default), 2 whenever
- *                    the operand allows it
+ *                    several snapshots with one access: 0 never, 1 automatic (default: whenever
+ *                    the operand allows it and holds at least 1 MB), 2 whenever the operand
+ *                    allows it
  *   "agg_parts"      timing aid only (results are incomplete unless 7): bit 0 hub segments,
  *                    bit 1 long rows, bit 2 short rows take part (default 7)
  */

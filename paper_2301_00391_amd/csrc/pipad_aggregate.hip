@@ -1035,14 +1035,11 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     if (!fused && !Y) return PIPAD_ERR_INVALID_ARG;  // the two-step form needs Y as its workspace
   }
   // Small F handed over as one concatenated operand: the coalescent kernel (snapshot groups).
-  // Policy (measured, see the design notes): with one snapshot per XCD a small-F matrix mostly
-  // fits that XCD's L2, so slicing wins unless the matrix is well beyond the L2 and the frame is
-  // dominated by its overlap part (the exclusive parts are walked lane by lane here).
-  int32_t max_delta = 0;
-  for (int t = 0; t < f->k; ++t) max_delta = std::max(max_delta, f->nnz_d[t]);
+  // Measured on every benchmark graph at F = 2, 6, 16: on that operand it beats the per-snapshot
+  // slices by 1.2-2.5x (a slice would use 4*F bytes of every k*F-float row it touches, and all
+  // XCDs would fetch the same lines); only operands of a few hundred KB are a tie.
   const int64_t mode = options().agg_coalescent;  // 0 never, 1 automatic, 2 whenever possible
-  const bool wanted = mode >= 2 || (mode == 1 && F <= 8 && (int64_t)f->n * F * 4 >= (8 << 20) &&
-                                    (int64_t)f->nnz_c >= 4 * (int64_t)max_delta);
+  const bool wanted = mode >= 2 || (mode == 1 && (int64_t)f->n * f->k * F * 4 >= ((int64_t)1 << 20));
   bool coalescent = wanted && !upd && F < 32 && f->k > 1 && ldx >= (int64_t)f->k * F &&
                     ldy >= (int64_t)f->k * F && (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32);
   for (int t = 1; t < f->k && coalescent; ++t)

@@ -9,6 +9,7 @@ on the synthetic generator instead of the paper's datasets.
   python -m paper_2301_00391_amd.sweeps features  # F x k table
   python -m paper_2301_00391_amd.sweeps sliding   # cost per new snapshot when the frame slides by one
   python -m paper_2301_00391_amd.sweeps workloads # the benchmark frames: one frame vs one snapshot at a time
+  python -m paper_2301_00391_amd.sweeps smallf    # F = 2 / 6 / 16: the coalescent kernel vs per-snapshot slices
 
 Every cell times ``pipad_frame_aggregate`` of one frame of k snapshots and, as the baseline, the
 same k snapshots aggregated one at a time (k frames of a single snapshot each, whose overlap part
@@ -38,7 +39,7 @@ def _time(fn, reps=5):
     return a.elapsed_time(b) / reps
 
 
-def _frame_times(snaps, k, feat, dev):
+def _frame_times(snaps, k, feat, dev, with_concatenated=False):
     n = snaps.n
     gs = [(torch.from_numpy(snaps.rowptr[t]).to(dev), torch.from_numpy(snaps.col[t]).to(dev))
           for t in range(k)]
@@ -62,11 +63,18 @@ def _frame_times(snaps, k, feat, dev):
             pipad.frame_aggregate(singles[t], xs[t], ys[t])
 
     t_single = _time(one_by_one)
+    # the physically concatenated (coalescent) operand: where the small-F kernel applies
+    t_concat = None
+    if with_concatenated:
+        yw = torch.empty_like(xw)
+        t_concat = _time(lambda: pipad.frame_aggregate(frame, xw, yw))
     nnz_c = int(frame.common()[1].numel())
     rate = nnz_c / float(np.mean([snaps.col[t].size for t in range(k)]))
     for f in singles:
         f.close()
     frame.close()
+    if with_concatenated:
+        return t_frame, t_single, rate, t_concat
     return t_frame, t_single, rate
 
 
@@ -89,14 +97,19 @@ def feature_sweep(dev):
     n, edges, churn = 200_000, 1_600_000, 0.03
     snaps = synth.graphs(n, edges, 8, churn, "chung-lu", (2.1, 16.0), seed=2)
     print(f"Chung-Lu gamma 2.1, N = {n}, {edges} undirected edges per snapshot, churn {churn:.0%}; "
-          "cell = frame ms / one-at-a-time ms (speedup)\n")
+          "cell = frame ms on k separate matrices [/ frame ms on the concatenated operand] / "
+          "one-at-a-time ms (speedup of the better frame)\n")
     print("| F | " + " | ".join(f"k = {k}" for k in (2, 4, 8)) + " |")
     print("|---|---|---|---|")
     for feat in (2, 6, 16, 32, 64, 128):
         cells = []
         for k in (2, 4, 8):
-            tf, ts, _ = _frame_times(snaps, k, feat, dev)
-            cells.append(f"{tf:.3f} / {ts:.3f} ({ts / tf:.2f}x)")
+            if feat < 32:
+                tf, ts, _, tc = _frame_times(snaps, k, feat, dev, with_concatenated=True)
+                cells.append(f"{tf:.3f} / {tc:.3f} / {ts:.3f} ({ts / min(tf, tc):.2f}x)")
+            else:
+                tf, ts, _ = _frame_times(snaps, k, feat, dev)
+                cells.append(f"{tf:.3f} / {ts:.3f} ({ts / tf:.2f}x)")
         print(f"| {feat} | " + " | ".join(cells) + " |", flush=True)
 
 
@@ -181,6 +194,37 @@ def workload_sweep(dev):
         del xb, xs, ys, gs
 
 
+def small_f_sweep(dev):
+    """The paper's own feature widths (F = 2, 6, 16, Section 5.1) on the benchmark graphs:
+    the coalescent kernel (one gather per overlap entry for several snapshots' rows, concatenated
+    operand) against the per-snapshot slices on the same operand and on k separate matrices."""
+    print("aggregation ms per frame\n")
+    print("| graph | F | concatenated operand, coalescent kernel | concatenated operand, slices | "
+          "k separate matrices, slices | what the automatic policy picks on the concatenated operand |")
+    print("|---|---|---|---|---|---|")
+    for name in ("large", "medium", "low-overlap", "small"):
+        cfg = synth.CONFIGS[name]
+        n, k = cfg.n, cfg.k
+        snaps = synth.graphs(n, cfg.edges, k, cfg.churn, cfg.model, cfg.params, cfg.seed)
+        gs = [(torch.from_numpy(snaps.rowptr[t]).to(dev), torch.from_numpy(snaps.col[t]).to(dev))
+              for t in range(k)]
+        frame = pipad.frame_build_overlap(gs)
+        for feat in (2, 6, 16):
+            xw = torch.rand((n, k, feat), device=dev) * 2 - 1
+            yw = torch.empty_like(xw)
+            xl = [xw[:, t, :].contiguous() for t in range(k)]
+            yl = [torch.empty_like(x) for x in xl]
+            pipad.set_option("agg_coalescent", 2)
+            t_co = _time(lambda: pipad.frame_aggregate(frame, xw, yw))
+            pipad.set_option("agg_coalescent", 0)
+            t_ws = _time(lambda: pipad.frame_aggregate(frame, xw, yw))
+            t_ls = _time(lambda: pipad.frame_aggregate(frame, xl, yl))
+            pipad.set_option("agg_coalescent", 1)
+            t_auto = _time(lambda: pipad.frame_aggregate(frame, xw, yw))
+            print(f"| {name} | {feat} | {t_co:.3f} | {t_ws:.3f} | {t_ls:.3f} | {t_auto:.3f} |", flush=True)
+        frame.close()
+
+
 def main(argv):
     if not torch.cuda.is_available():
         print("sweeps need a GPU", file=sys.stderr)
@@ -195,6 +239,8 @@ def main(argv):
         sliding_sweep(dev)
     elif which == "workloads":
         workload_sweep(dev)
+    elif which == "smallf":
+        small_f_sweep(dev)
     else:
         print(__doc__, file=sys.stderr)
         return 2
