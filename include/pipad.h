@@ -193,8 +193,8 @@ const char *pipad_last_hip_error(void);
  *                    to have at least 8 slices or "agg_order" asks for it)
  *   "agg_order"      order of the slices in time: 0 all snapshots side by side (one per XCD),
  *                    1 one snapshot after the other (the whole chip on one matrix, 32-column
- *                    slices), 2 automatic (default): 1 for matrices of 64 MB and more per snapshot
- *                    or more than 64 columns
+ *                    slices), 2 automatic (default): 1 for more than 64 columns, or more than 32
+ *                    columns and matrices of 64 MB and more per snapshot
  *   "agg_generic"    1 forces the bounds-checked kernel with 64-bit addresses (default 0: only for
  *                    matrices of 4 GB and more)
  *   "agg_coalescent" kernel for F < 32 on the concatenated operand that gathers the rows of

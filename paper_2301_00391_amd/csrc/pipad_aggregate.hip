@@ -1065,10 +1065,12 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   // Order of the slices in time.  Side by side (every XCD on its own snapshot) or one snapshot
   // after the other (the whole chip on one matrix, in 32-column slices: an XCD's L2 then holds
   // twice as many - half as wide - hot rows, and the memory-side cache sees one matrix at a time).
-  // Measured: the second wins by 4-19 % when a snapshot's matrix is large (N*F*4 >= 64 MB) or has
-  // more than 64 columns, and loses 7 % on a 51 MB matrix of 64 columns.
+  // Measured: the second wins by 4-19 % for rows of more than 64 columns and for 64-column
+  // matrices of 64 MB and more per snapshot, is level on a 51 MB matrix of 64 columns, and loses
+  // up to 25 % at 32 columns and fewer (one slice per snapshot: nothing to narrow).
   a.order = (int32_t)options().agg_order;
-  if (a.order >= 2) a.order = (F > 64 || (int64_t)f->n * F * 4 >= ((int64_t)64 << 20)) ? 1 : 0;
+  if (a.order >= 2)
+    a.order = (F > 64 || (F > 32 && (int64_t)f->n * F * 4 >= ((int64_t)64 << 20))) ? 1 : 0;
   if (a.order == 1 && options().slice_cols == 0 && F > 32) max_cols = 32;
   if (fused) max_cols = 64;
   const int cols = std::min(F, max_cols);
@@ -1087,9 +1089,11 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     const int64_t enough = 4 * 8192;  // waves
     a.batch_short = kShortRowsPerWave;
     a.batch_long = kLongRowsPerWave;
+    // (one snapshot after the other: what runs together is one snapshot's slices)
+    const int together = a.order == 1 && !coalescent ? a.fchunks : a.nslices;
     auto waves = [&]() {
       return ((int64_t)(f->n_short + a.batch_short - 1) / a.batch_short +
-              (int64_t)(f->n_long + a.batch_long - 1) / a.batch_long + f->n_items) * a.nslices;
+              (int64_t)(f->n_long + a.batch_long - 1) / a.batch_long + f->n_items) * together;
     };
     while (waves() < enough && (a.batch_short > nteams || a.batch_long > 1)) {
       if (a.batch_short > nteams) a.batch_short >>= 1;
