@@ -41,7 +41,9 @@ typedef enum pipad_status {
   PIPAD_ERR_BAD_CSR = -2,     /* PIPAD_VALIDATE found a snapshot that is not canonical          */
   PIPAD_ERR_ALLOC = -3,       /* device allocation failed (callback returned NULL / hipMalloc)  */
   PIPAD_ERR_TOO_LARGE = -4,   /* a size does not fit the int32 index space                      */
-  PIPAD_ERR_HIP = -5          /* a HIP runtime call failed; see pipad_last_hip_error()          */
+  PIPAD_ERR_HIP = -5,         /* a HIP runtime call failed; see pipad_last_hip_error()          */
+  PIPAD_ERR_SCRATCH = -6      /* pipad_frame_aggregate_static: the partial sums of this frame   *
+                               * and F do not fit the fixed scratch array; nothing was enqueued */
 } pipad_status;
 
 /* One sparse 0/1 pattern in CSR.  Used for the input snapshots and for borrowed views of a
@@ -130,6 +132,24 @@ int pipad_frame_shape(const pipad_frame_t *frame, int32_t *n, int32_t *k);
  */
 int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *const *X,
                           int64_t ldx, float *const *Y, int64_t ldy, void *stream);
+
+/* pipad_frame_aggregate for callers that cannot allocate device memory: code under HIP graph
+ * (stream) capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results, but the partial sums of split rows go to a fixed array of
+ * PIPAD_STATIC_SCRATCH_BYTES that is part of the library's device code (every GPU the library
+ * runs on holds its own copy until the process ends) instead of the frame's growable buffer, and
+ * the allocator callback is never called.  The call issues no hipMalloc / hipFree and no other
+ * allocating routine; the array's address on a device is looked up once, at the first
+ * pipad_frame_build_overlap or pipad_frame_aggregate_static on that device.
+ *   Returns PIPAD_ERR_SCRATCH, with nothing enqueued, when the frame needs more than the array
+ *   holds: (number of split-row segments) * k * (F rounded up to the slice width) floats.
+ *   All calls on one GPU share the array: calls that overlap in time on that GPU (different
+ *   streams, or different frames) race on it and give wrong results; calls ordered on one stream
+ *   are safe.  Nothing in the array has to be cleared between calls: every partial sum is written
+ *   before it is read within the same call. */
+#define PIPAD_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int pipad_frame_aggregate_static(const pipad_frame_t *frame, int32_t F, const float *const *X,
+                                 int64_t ldx, float *const *Y, int64_t ldy, void *stream);
 
 /* One GCN layer for every snapshot of the frame: the aggregation above followed by the update of
  * Eq. 1, a fully connected layer whose weights all snapshots of the frame share (Section 2.1;

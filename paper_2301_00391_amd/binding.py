@@ -50,6 +50,8 @@ SIGNATURES = {
     "pipad_frame_shape": (ctypes.c_int, [_vp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]),
     "pipad_frame_aggregate": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_vp), _i64,
                                              ctypes.POINTER(_vp), _i64, _vp]),
+    "pipad_frame_aggregate_static": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_vp), _i64,
+                                                    ctypes.POINTER(_vp), _i64, _vp]),
     "pipad_frame_aggregate_update": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_vp), _i64, _vp, _i64,
                                                     _vp, _i32, ctypes.POINTER(_vp), _i64,
                                                     ctypes.POINTER(_vp), _i64, _vp]),
@@ -268,10 +270,13 @@ def _operand(x: Features, n: int, k: int, name: str) -> Tuple[List[int], int, in
     return ptrs, int(ld), int(F)
 
 
-def frame_aggregate(frame: Frame, X: Features, Y: Optional[Features] = None, stream=None) -> Features:
+def frame_aggregate(frame: Frame, X: Features, Y: Optional[Features] = None, stream=None,
+                    static_scratch: bool = False) -> Features:
     """pipad_frame_aggregate: Y_t = D_t^-1/2 (A_t + I) D_t^-1/2 X_t for every snapshot of the frame.
 
-    Y is allocated like X when not given.  Only enqueues work on the stream."""
+    Y is allocated like X when not given.  Only enqueues work on the stream.
+    ``static_scratch=True`` calls pipad_frame_aggregate_static instead (no device allocation inside
+    the library; pass Y, or this wrapper allocates it before the call)."""
     lib = load_library()
     n, k = frame.n, frame.k
     xp, ldx, F = _operand(X, n, k, "X")
@@ -286,7 +291,8 @@ def frame_aggregate(frame: Frame, X: Features, Y: Optional[Features] = None, str
     xa = (_vp * k)(*xp)
     ya = (_vp * k)(*yp)
     with torch.cuda.device(frame.device):
-        _check(lib.pipad_frame_aggregate(frame._h, F, xa, ldx, ya, ldy, _stream_handle(stream)))
+        fn = lib.pipad_frame_aggregate_static if static_scratch else lib.pipad_frame_aggregate
+        _check(fn(frame._h, F, xa, ldx, ya, ldy, _stream_handle(stream)))
     return Y
 
 

@@ -37,6 +37,7 @@
 // With fewer than 8 slices the slice width drops to 32 columns (still whole 128-byte lines).
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 
 #include "pipad_internal.h"
 
@@ -982,8 +983,36 @@ int launch_coalescent(const AggArgs &a, hipStream_t st) {
 
 }  // namespace
 
+// ---- the fixed scratch array of pipad_frame_aggregate_static -----------------------------------
+// One array per GPU (every device that loads the library's code holds its own copy until the
+// process ends).  The array's name is only a handle in host code: its device address is looked up
+// once per device, with that device current, and only that address is ever handed to a kernel.
+constexpr size_t kStaticScratchBytes = PIPAD_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(float **ptr, size_t *floats) {
+  int dev = -1;
+  PIPAD_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return PIPAD_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    PIPAD_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return PIPAD_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = static_cast<float *>(g_scratch_ptr[dev]);
+  *floats = kStaticScratchBytes / sizeof(float);
+  return PIPAD_OK;
+}
+
 int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t ldx,
-                     float *const *Y, int64_t ldy, hipStream_t st, const UpdateSpec *upd) {
+                     float *const *Y, int64_t ldy, hipStream_t st, const UpdateSpec *upd,
+                     float *fixed_scratch, size_t fixed_scratch_floats) {
   if (f->n == 0) return PIPAD_OK;
   AggArgs a;
   std::memset(&a, 0, sizeof(a));
@@ -1105,7 +1134,9 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
 
   // scratch for the partial sums of hub segments: n_items x nslices x slice width
   const size_t need = (size_t)f->n_items * (size_t)a.nslices * (size_t)sw;
-  if (need > f->partial_floats) {
+  if (fixed_scratch) {
+    if (need > fixed_scratch_floats) return PIPAD_ERR_SCRATCH;
+  } else if (need > f->partial_floats) {
     void *ptr = nullptr;
     if (f->alloc) {
       // the caller's allocator owns the memory; a smaller buffer from before stays with it
@@ -1125,7 +1156,7 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     f->partial = static_cast<float *>(ptr);
     f->partial_floats = need;
   }
-  a.partial = f->partial;
+  a.partial = fixed_scratch ? fixed_scratch : f->partial;
   if (coalescent)
     return cvec == 4 ? launch_coalescent<4>(a, st)
                      : cvec == 2 ? launch_coalescent<2>(a, st) : launch_coalescent<1>(a, st);

@@ -100,6 +100,27 @@ int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *co
                                  static_cast<hipStream_t>(stream));
 }
 
+int pipad_frame_aggregate_static(const pipad_frame_t *frame, int32_t F, const float *const *X,
+                                 int64_t ldx, float *const *Y, int64_t ldy, void *stream) {
+  if (!frame || !X || !Y || F < 1 || ldx < F || ldy < F) return PIPAD_ERR_INVALID_ARG;
+  if (frame->n > 0)
+    for (int t = 0; t < frame->k; ++t)
+      if (!X[t] || !Y[t]) return PIPAD_ERR_INVALID_ARG;
+  if ((int64_t)frame->n * ldx >= ((int64_t)1 << 40) || (int64_t)frame->n * ldy >= ((int64_t)1 << 40))
+    return PIPAD_ERR_TOO_LARGE;
+  if (frame->n == 0) return PIPAD_OK;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return pipad::hip_fail(hipGetLastError(), "hipGetDevice");
+  if (dev != frame->device) return PIPAD_ERR_INVALID_ARG;
+  float *scratch_ptr = nullptr;
+  size_t scratch_floats = 0;
+  const int rc = pipad::static_scratch(&scratch_ptr, &scratch_floats);
+  if (rc != PIPAD_OK) return rc;
+  return pipad::aggregate_launch(const_cast<pipad_frame *>(frame), F, X, ldx, Y, ldy,
+                                 static_cast<hipStream_t>(stream), nullptr, scratch_ptr,
+                                 scratch_floats);
+}
+
 int pipad_frame_aggregate_update(const pipad_frame_t *frame, int32_t F, const float *const *X,
                                  int64_t ldx, const float *W, int64_t ldw, const float *bias,
                                  int32_t Fo, float *const *A, int64_t lda, float *const *H,
@@ -147,6 +168,7 @@ const char *pipad_strerror(int status) {
     case PIPAD_ERR_ALLOC: return "device allocation failed";
     case PIPAD_ERR_TOO_LARGE: return "size exceeds the int32 index space";
     case PIPAD_ERR_HIP: return "HIP runtime error";
+    case PIPAD_ERR_SCRATCH: return "the fixed scratch array is too small for this frame and F";
     default: return "unknown status";
   }
 }

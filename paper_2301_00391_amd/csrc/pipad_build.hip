@@ -653,6 +653,13 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     return code;
   };
   if (hipGetDevice(&f->device) != hipSuccess) return fail(hip_fail(hipGetLastError(), "hipGetDevice"));
+  {
+    // set-up of pipad_frame_aggregate_static on this device: look up the fixed scratch array's
+    // address now, so that the entry point itself has nothing left to initialise
+    float *unused_ptr = nullptr;
+    size_t unused_floats = 0;
+    (void)static_scratch(&unused_ptr, &unused_floats);
+  }
 
   // ---- sizes known up front: row pointers and D^-1/2 (persistent), all temporaries
   Parts p;

@@ -152,9 +152,16 @@ struct UpdateSpec {
   int64_t ldh;
 };
 // Y may be null when `update` is given and the shape allows the fused kernel.
+// `fixed_scratch` (with its capacity in floats), when given, replaces the frame's own growable
+// scratch buffer: the call then allocates nothing and fails with PIPAD_ERR_SCRATCH when the
+// partial sums do not fit.
 int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t ldx,
                      float *const *Y, int64_t ldy, hipStream_t stream,
-                     const UpdateSpec *update = nullptr);
+                     const UpdateSpec *update = nullptr, float *fixed_scratch = nullptr,
+                     size_t fixed_scratch_floats = 0);
+
+// Address, on the current device, of the library's fixed scratch array (resolved once per device).
+int static_scratch(float **ptr, size_t *floats);
 }
 
 #endif  // PIPAD_INTERNAL_H_
