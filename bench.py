@@ -61,6 +61,70 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def _timed(torch, fn, reps):
+    """Mean milliseconds of fn() over reps launches on the current stream (one warm-up first)."""
+    fn()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    b.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def measure_ceilings(pipad, torch, full: bool):
+    """What the memory system of this GPU delivers for the two kinds of traffic the aggregation
+    consists of (kernels of include/pipad_ceilings.h): a streaming read, and gathers of feature
+    rows in the aggregation kernel's access shape from working sets that fit one L2, the
+    memory-side cache, or only HBM.  Returns a dict; ``full`` adds the whole sweep."""
+    import ctypes
+    lib = pipad.load_library()
+    dev = torch.device("cuda:0")
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    sink = torch.empty(lib.pipad_ceiling_sink_floats(), dtype=torch.float32, device=dev)
+    res = {}
+    src = torch.ones(1 << 29, dtype=torch.float32, device=dev)  # 2 GiB
+    ms = _timed(torch, lambda: lib.pipad_ceiling_stream_read(src.data_ptr(), src.numel() * 4,
+                                                             sink.data_ptr(), st), 10)
+    res["stream_read_GBps"] = src.numel() * 4 / ms / 1e6
+    count = 1 << 24
+    gen = torch.Generator(device="cpu").manual_seed(7)
+
+    def gather(row_floats, stride, ws_bytes, classes):
+        rows = max(1, ws_bytes // (stride * 4))
+        table = src[: rows * stride]
+        if classes:  # section x of the index only touches the x-th eighth of the table
+            per = count // classes
+            base = (torch.arange(classes).repeat_interleave(per) * (rows // classes))
+            idx = (torch.randint(0, max(1, rows // classes), (count,), generator=gen) + base)
+        else:
+            idx = torch.randint(0, rows, (count,), generator=gen)
+        idx = idx.to(torch.int32).to(dev)
+        rc = []
+        ms = _timed(torch, lambda: rc.append(lib.pipad_ceiling_gather(
+            table.data_ptr(), rows, row_floats, stride, idx.data_ptr(), count, classes,
+            sink.data_ptr(), st)), 5)
+        assert all(r == 0 for r in rc), rc
+        return count * row_floats * 4 / ms / 1e6  # GB/s of gathered bytes
+
+    MiB = 1 << 20
+    # the three numbers the roofline block uses: 256-byte rows from an L2-, a MALL- and an HBM-sized set
+    res["gather_256B_L2_GBps"] = gather(64, 64, 2 * MiB, 0)
+    res["gather_256B_MALL_GBps"] = gather(64, 64, 64 * MiB, 0)
+    res["gather_256B_HBM_GBps"] = gather(64, 64, 2048 * MiB - 4096, 0)
+    if full:
+        sweep = []
+        for row_floats, stride in ((64, 64), (64, 96), (32, 32)):
+            for ws in (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 64, 128, 256, 1024, 2047):
+                for classes in (0, 8):
+                    sweep.append({"row_bytes": row_floats * 4, "stride_bytes": stride * 4,
+                                  "working_set_MiB": ws, "xcd_classes": classes,
+                                  "GBps": gather(row_floats, stride, ws * MiB, classes)})
+        res["sweep"] = sweep
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,16 +134,18 @@ def main() -> int:
     ap.add_argument("--epochs", type=int, default=1, help="aggregations per overlap extraction")
     ap.add_argument("--layout", default="list", choices=["wide", "list"],
                     help="wide: one [N, k, F] coalescent operand; list: k separate [N, F] matrices")
-    ap.add_argument("--short-max", type=int, default=-1)
-    ap.add_argument("--nt", type=int, default=-1)
-    ap.add_argument("--hub-threshold", type=int, default=-1)
-    ap.add_argument("--hub-segment", type=int, default=-1)
+    ap.add_argument("--opt", action="append", default=[], metavar="KEY=VALUE",
+                    help="library option set before the frames are built (pipad_set_option), "
+                         "e.g. --opt short_max=16 --opt slice_cols=32")
     ap.add_argument("--row-stride", default="auto", choices=["auto", "dense"],
                     help="rows of X: padded to an odd number of 128-byte lines (auto) or F floats")
     ap.add_argument("--update", type=int, default=0, metavar="FO",
                     help="time pipad_frame_aggregate_update (the GCN layer with FO output columns: "
                          "aggregation + fully connected update) instead of the aggregation alone")
     ap.add_argument("--cold", action="store_true", help="flush the caches between steps")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="only measure the streaming and gather ceilings of this GPU (full sweep) "
+                         "and print them as one JSON line")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--cpu-threads", type=int, default=0, help="oracle threads (0 = all)")
@@ -98,14 +164,20 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 3
     pipad.load_library()
-    if args.short_max >= 0:
-        pipad.set_option("short_max", args.short_max)
-    if args.nt >= 0:
-        pipad.set_option("agg_nt", args.nt)
-    if args.hub_threshold >= 0:
-        pipad.set_option("hub_threshold", args.hub_threshold)
-    if args.hub_segment >= 0:
-        pipad.set_option("hub_segment", args.hub_segment)
+    if args.ceilings:
+        res = measure_ceilings(pipad, torch, full=True)
+        log("| row bytes | stride | working set MiB | XCD classes | gathered GB/s |")
+        log("|---|---|---|---|---|")
+        for r in res["sweep"]:
+            log(f"| {r['row_bytes']} | {r['stride_bytes']} | {r['working_set_MiB']} | "
+                f"{r['xcd_classes']} | {r['GBps']:.0f} |")
+        print(json.dumps(res), flush=True)
+        return 0
+    options = {}
+    for item in args.opt:
+        key, _, val = item.partition("=")
+        pipad.set_option(key, int(val))
+        options[key] = int(val)
     dev = torch.device("cuda:0")
     cfg = synth.CONFIGS[args.workload]
     n, k, F = cfg.n, cfg.k, cfg.feat
@@ -241,7 +313,7 @@ def main() -> int:
         "config": {"workload": args.workload, "n": n, "k": k, "F": F, "model": None,
                    "generator": cfg.model, "edges_per_snapshot": cfg.edges, "churn": cfg.churn,
                    "seed": cfg.seed, "layout": args.layout, "x_row_stride_floats": x_stride,
-                   "epochs_per_build": args.epochs,
+                   "epochs_per_build": args.epochs, "options": options,
                    "frames": nframes, "fused_update_cols": Fo, "cache": "cold" if args.cold else "as left by the previous step",
                    "nnz_common": nnz_c, "nnz_exclusive": nnz_d,
                    "overlap_rate": nnz_c / (sum(nnz_t) / k)},

@@ -200,29 +200,27 @@ const char *pipad_strerror(int status);
 /* Text of the last HIP runtime error seen by the calling thread ("" if none). */
 const char *pipad_last_hip_error(void);
 
-/* Tuning knobs for measurements; process-wide, not thread-safe.  Unknown keys and negative values
- * return PIPAD_ERR_INVALID_ARG.  The three length thresholds take effect for frames built
- * afterwards.  Keys:
- *   "short_max"      rows with at most this many (common + longest exclusive) entries are walked
- *                    by one small lane team, several rows per wave (default 32)
- *   "hub_threshold"  rows with more entries than this are split into segments (default 2048)
- *   "hub_segment"    entries per segment of a split row (default 1024)
+/* Tuning knobs; process-wide, not thread-safe.  A frame takes a copy of all of them when it is
+ * built (pipad_frame_build_overlap; a transposed frame inherits its source's) and never looks at
+ * the process-wide values again, so changing a knob affects frames built afterwards only.
+ * Unknown keys, negative values and values beyond a key's range return PIPAD_ERR_INVALID_ARG.
+ * Keys (row lengths count common + longest exclusive entries of a row; at most 2^30):
+ *   "short_max"      rows with at most this many entries are walked whole by one small lane team,
+ *                    several rows per wave (default 32)
+ *   "mid_max"        longer rows are split by column class (8 partial sums per row, each walked
+ *                    on the XCD that caches its class); up to this length a lane team walks a
+ *                    class part, beyond it a whole wave (default 256; below short_max: as short_max)
+ *   "hub_threshold"  rows with more entries than this are first cut into units (default 8192)
+ *   "hub_segment"    entries per unit of a cut row (default 8192)
  *   "agg_nt"         bit 0: non-temporal stores for Y; bit 1: non-temporal loads for the index and
  *                    scale streams (default 0)
- *   "slice_cols"     feature columns per slice, at most 64 (default 0: 64, or 32 when that is needed
- *                    to have at least 8 slices or "agg_order" asks for it)
- *   "agg_order"      order of the slices in time: 0 all snapshots side by side (one per XCD),
- *                    1 one snapshot after the other (the whole chip on one matrix, 32-column
- *                    slices), 2 automatic (default): 1 for more than 64 columns, or more than 32
- *                    columns and matrices of 64 MB and more per snapshot
+ *   "slice_cols"     feature columns per slice, 1..64 (default 0 = 64)
  *   "agg_generic"    1 forces the bounds-checked kernel with 64-bit addresses (default 0: only for
  *                    matrices of 4 GB and more)
  *   "agg_coalescent" kernel for F < 32 on the concatenated operand that gathers the rows of
  *                    several snapshots with one access: 0 never, 1 automatic (default: whenever
  *                    the operand allows it and holds at least 1 MB), 2 whenever the operand
  *                    allows it
- *   "agg_parts"      timing aid only (results are incomplete unless 7): bit 0 hub segments,
- *                    bit 1 long rows, bit 2 short rows take part (default 7)
  */
 int pipad_set_option(const char *key, int64_t value);
 int pipad_get_option(const char *key, int64_t *value);

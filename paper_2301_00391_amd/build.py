@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpipad.so")
-SOURCES = ["pipad_api.hip", "pipad_build.hip", "pipad_aggregate.hip", "pipad_transpose.hip"]
+SOURCES = ["pipad_api.hip", "pipad_build.hip", "pipad_aggregate.hip", "pipad_transpose.hip",
+           "pipad_ceilings.hip"]
 
 
 def hipcc() -> str:
@@ -18,6 +19,23 @@ def hipcc() -> str:
         if cand and os.path.exists(cand):
             return cand
     raise RuntimeError("hipcc not found: libpipad needs the ROCm toolchain")
+
+
+def check_private_memory(remarks: str, limit: int = 64) -> None:
+    """Fails the build when a kernel keeps more than a few spilled registers in private (scratch)
+    memory.  The aggregation kernels take their arguments as one large struct; if the compiler
+    cannot prove that it is only read at constant offsets it copies the whole struct (over 2 KB)
+    into every lane's private memory, which costs an order of magnitude in run time and no test
+    would notice."""
+    name = None
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split()[0]
+        elif "ScratchSize [bytes/lane]:" in line and name:
+            size = int(line.split("ScratchSize [bytes/lane]:")[1].split()[0])
+            if size > limit and "5pipad" in name:  # this library's kernels (namespace pipad)
+                raise RuntimeError(f"kernel {name} uses {size} bytes of private memory per lane "
+                                   f"(limit {limit}): kernel arguments copied to scratch?")
 
 
 def build(verbose: bool = False) -> str:
@@ -32,14 +50,18 @@ def build(verbose: bool = False) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [hipcc(), *flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc(), *flags, "-Rpass-analysis=kernel-resource-usage", "-c",
+               os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
-        procs.append((cmd, subprocess.Popen(cmd)))
+        procs.append((cmd, subprocess.Popen(cmd, stderr=subprocess.PIPE, text=True)))
         objs.append(obj)
     for cmd, p in procs:
-        if p.wait() != 0:
+        _, err = p.communicate()
+        if p.returncode != 0:
+            sys.stderr.write(err)
             raise RuntimeError("hipcc failed: " + " ".join(cmd))
+        check_private_memory(err)
     link = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:
         print(" ".join(link), flush=True)

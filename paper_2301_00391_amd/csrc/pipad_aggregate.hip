@@ -16,63 +16,90 @@
 // contraction), so there is no MFMA.
 //
 // How one launch covers the frame.  The coalescent feature row of a node (k snapshots x F
-// columns) is cut into *slices* of at most 64 columns of one snapshot.  A workgroup works on ONE
-// slice, and consecutive workgroups take consecutive slices: workgroups are dealt round-robin to
-// the 8 XCDs, each with a private 4 MB L2, so with k = 8 every XCD gathers one snapshot's slice of
-// every row and its L2 only has to hold 1/8 of each hot row.  The overlap CSR is read from HBM
-// once and reaches the other XCDs through the memory-side cache.
+// columns) is cut into *slices* of at most 64 columns of one snapshot, and the launch goes through
+// the slices one after the other (workgroups are dispatched in index order): the whole chip works
+// on one snapshot's matrix at a time, so the caches see one matrix instead of k.
+//
+// Column classes.  The chip has 8 XCDs, each with a private 4 MB L2; workgroup b runs on XCD
+// b mod 8.  A feature row that all 8 L2s cache occupies 8 times its size, and the gathered rows of
+// a power-law graph do not fit one L2.  So every column belongs to one of 8 classes (a hash of its
+// index), the entries of the long ("hub") rows are stored a second time, grouped by class, and
+// the part of a row that falls into class x is walked by a workgroup whose index is x mod 8: XCD x
+// only ever gathers class x, and the 8 L2s together act as one cache of 32 MB.  The price is that
+// such a row is summed in 8 parts; the partial sums go through a scratch buffer and a second small
+// kernel adds them in a fixed order, applies the self-loop term and the row scale, and stores the
+// row.  Measured, the 8 partial sums (written and read back through memory) only pay for rows of
+// several hundred entries, so the other rows - most rows, and on graphs of moderate skew most
+// entries - are walked whole.
 //
 // Work items of a slice, by row length L = common + longest exclusive row (binned by the build):
-//   short rows  a team of LS lanes (LS * VEC = slice width) per row, 64/LS rows side by side in
-//               a wave, 64 rows per wave; row metadata for the 64 rows is loaded in one go.
-//   long rows   a wave per row, 8 rows per wave; the 64/LS lane teams take different entries and
-//               are summed with cross-lane shuffles.
-//   hub rows    cut into segments (the role the paper's sliced CSR plays for load balance,
-//               Section 4.1); a wave per segment writes a partial sum, and a second small kernel
-//               adds the partials of a row in a fixed order.
+//   hub rows    split by class; a wave per class part, the 64/LS lane teams take different
+//               entries and are summed with cross-lane shuffles.  Rows beyond hub_threshold
+//               entries are first cut into units (the role the paper's sliced CSR plays for load
+//               balance, Section 4.1).
+//   mid rows    walked whole by a wave, the same way; self-loop, row scale and store at once.
+//   short rows  walked whole: a team of LS lanes (LS * VEC = slice width) per row, 64/LS rows
+//               side by side, row metadata for a whole batch loaded in one go.
 // Entries are fetched a team-wide chunk at a time (one coalesced load of indices and scales),
 // turned into 32-bit row offsets and handed to the lane teams through LDS, so the inner loop
 // issues only the 16-byte row gathers (the "vector memory instruction" of Section 4.2), four of
 // them in flight per lane; the next chunk and the next row's first chunk are requested early.
-// With fewer than 8 slices the slice width drops to 32 columns (still whole 128-byte lines).
 #include <algorithm>
 #include <cstring>
 #include <mutex>
 
 #include "pipad_internal.h"
 
+#ifndef PIPAD_PARTIAL_NT
+#define PIPAD_PARTIAL_NT 0
+#endif
+
 namespace pipad {
 namespace {
 
 // Most rows a wave takes one after the other (lane l holds the metadata of row l of the batch).
 // The launch lowers these for small frames, so that the chip still gets enough waves.
-constexpr int kShortRowsPerWave = 64;
-constexpr int kLongRowsPerWave = 8;
+constexpr int kShortRowsPerWave = 64;  // short rows, a lane team per row
+constexpr int kLongRowsPerWave = 8;    // mid rows, a wave per row
+#ifndef PIPAD_WIDE_BATCH
+#define PIPAD_WIDE_BATCH 4
+#endif
+constexpr int kWideUnitsPerWave = PIPAD_WIDE_BATCH;   // class parts of hub units, a wave per part
 
 struct AggArgs {
   int32_t n, k, F;
   int32_t ls_log2;    // log2 of the lanes per slice row
   int32_t fchunks;    // slices per snapshot = ceil(F / (LS * VEC))
   int32_t nslices;    // k * fchunks
-  int32_t seg;        // entries per hub segment
   int32_t n_short, n_long, n_items, n_hub;
-  int32_t blocks_items, blocks_long;  // workgroups per slice for the first two item kinds
-  int32_t batch_short, batch_long;    // rows per wave
-  int32_t order;                      // 0: slices side by side, 1: one snapshot after the other
-  int64_t blocks_per_slice;           // workgroups one slice takes (all three item kinds)
+  // workgroups of one slice ("phase"): for every sub class in turn 8 * blocks_wide for the hub
+  // units (workgroup r of them takes XCD r mod 8's class), then blocks_mid for the mid rows, then
+  // blocks_short (padded so that every phase starts at a multiple of 8 and the XCD a workgroup is
+  // meant for is the one it runs on)
+  int32_t blocks_wide, blocks_mid, blocks_short;
+  int32_t batch_short, batch_mid, batch_wide;  // rows / class parts per wave
+  int64_t blocks_per_phase;
+  int32_t sub_log2;   // log2 of the sub classes per XCD
+  int32_t nclass;     // 8 << sub_log2
+  int64_t nv;         // class parts per part of the frame = nclass * n_units
+  int64_t nvp;        // partial sums per slice: nclass per hub unit
   int32_t nt;         // non-temporal hints (bit 0: Y stores, bit 1: index streams)
-  int32_t parts;      // timing aid: which kinds of work items run (all in normal use)
   int32_t sg;         // coalescent kernel: snapshots per lane team (slices are snapshot groups)
   int64_t ldx, ldy;
   const int32_t *rowptr_c, *col_c;
   const float *dinv;
   const int32_t *rows_short, *rows_long;
-  const int32_t *item_row, *item_seg, *hub_rows, *hub_item_off;
+  const int32_t *item_row, *item_v0, *item_v1, *hub_rows, *hub_item_off;
+  const uint32_t *sptr;   // class parts of the split rows: see pipad_frame
+  const int32_t *scol;
+  const float *swd;
+  int64_t total_c;        // entries of the common region of scol
   float *partial;
   const int32_t *rowptr_d[PIPAD_MAX_K];
   const int32_t *col_d[PIPAD_MAX_K];
   const float *wc[PIPAD_MAX_K];
   const float *wd[PIPAD_MAX_K];
+  const float *swc[PIPAD_MAX_K];
   const float *X[PIPAD_MAX_K];
   float *Y[PIPAD_MAX_K];   // aggregation results (optional when the update is fused in)
   // fused update: H_t = Y_t W + bias
@@ -134,24 +161,28 @@ template <> struct V<1> {
 
 // What a lane needs to know about its slice.
 struct Slice {
+  int t;                    // snapshot
   const float *xt;          // X_t (the same for the whole workgroup)
   const float *xb;          // X_t + feature column of this lane
   float *yb;                // Y_t + feature column of this lane (null: not wanted)
   float *ht;                // H_t (fused update only)
   const float *dv;          // dinv_t
-  const float *wc, *wd;     // per-entry column scales of the common / exclusive part
-  const int32_t *rpd, *cd;  // exclusive CSR of snapshot t
+  const float *wc, *wd;     // per-entry column scales of the common / exclusive part (short rows)
+  const int32_t *rpd, *cd;  // exclusive CSR of snapshot t (short rows)
+  const float *swc;         // column scales of the common region of the class-grouped entries
   int fcol;
   bool fvalid;              // the lane's columns exist (F need not fill the last slice)
 };
 
-__device__ inline Slice slice_setup(const AggArgs &a, int slice, int fl, int vec) {
+// slice -> (snapshot, column chunk): slice = chunk * k + snapshot
+__device__ __forceinline__ Slice slice_setup(const AggArgs &a, int slice, int fl, int vec) {
   Slice s;
-  // slice -> (snapshot, column chunk), snapshot fastest: workgroup b works on slice b mod nslices
-  // and lands on XCD b mod 8, so with k a multiple of 8 all column chunks of a snapshot share an
-  // XCD, whose L2 then serves that snapshot's index and scale streams to the later chunks
+  // (the slice is the same for the whole workgroup: saying so lets the per-snapshot pointers come
+  // from the kernel arguments through the scalar unit)
+  slice = __builtin_amdgcn_readfirstlane(slice);
   const int fc = slice / a.k;
   const int t = slice - fc * a.k;
+  s.t = t;
   s.fcol = (fc << a.ls_log2) * vec + fl * vec;
   s.fvalid = s.fcol < a.F;
   const int col = s.fvalid ? s.fcol : 0;  // idle lanes read column 0 and never store
@@ -164,6 +195,7 @@ __device__ inline Slice slice_setup(const AggArgs &a, int slice, int fl, int vec
   s.wd = a.wd[t];
   s.rpd = a.rowptr_d[t];
   s.cd = a.col_d[t];
+  s.swc = a.swc[t];
   return s;
 }
 
@@ -180,7 +212,7 @@ struct Staged {
 
 // Entry base + q of a list, or (own row, weight 0) past its end: such a filler may be gathered
 // harmlessly, which lets the FAST inner loop run without bounds checks.
-__device__ inline Raw fetch_entry(const int32_t *__restrict__ col, const float *__restrict__ w,
+__device__ __forceinline__ Raw fetch_entry(const int32_t *__restrict__ col, const float *__restrict__ w,
                                   int32_t start, int32_t len, int32_t pos, int32_t self, bool nt) {
   Raw r;
   r.c = self;
@@ -209,7 +241,7 @@ __device__ inline Raw fetch_entry(const int32_t *__restrict__ col, const float *
 // one LDS read, one add, one 16-byte gather and VEC fused multiply-adds per entry.
 // The FAST inner loop needs nslots * UNR to divide team_lanes.
 template <int VEC, int UNR, bool FAST>
-__device__ inline void walk(const int32_t *__restrict__ col, const float *__restrict__ w,
+__device__ __forceinline__ void walk(const int32_t *__restrict__ col, const float *__restrict__ w,
                             int32_t start, int32_t len, Raw first, int team_base, int team_lanes,
                             int q, int slot, int nslots, const Slice &s, int64_t ldx, int32_t self,
                             bool nt, Staged *lds, typename V<VEC>::T &acc) {
@@ -276,7 +308,7 @@ struct Sink {
 typedef float mfma_f4 __attribute__((ext_vector_type(4)));
 
 template <int KS>  // k values per lane group = lanes per row
-__device__ inline void sink_flush_ks(const AggArgs &a, const Slice &s, Sink &k, int lane) {
+__device__ __forceinline__ void sink_flush_ks(const AggArgs &a, const Slice &s, Sink &k, int lane) {
   const int m = lane & 15, g = lane >> 4;
   float av[KS];
 #pragma unroll
@@ -308,7 +340,7 @@ __device__ inline void sink_flush_ks(const AggArgs &a, const Slice &s, Sink &k, 
   }
 }
 
-__device__ inline void sink_flush(const AggArgs &a, const Slice &s, Sink &k, int lane) {
+__device__ __forceinline__ void sink_flush(const AggArgs &a, const Slice &s, Sink &k, int lane) {
   if (k.cnt == 0) return;
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   switch (a.ls_log2) {
@@ -321,7 +353,7 @@ __device__ inline void sink_flush(const AggArgs &a, const Slice &s, Sink &k, int
 }
 
 // Self-loop term and row scale; the row goes to the tile (and to Y_t when that is wanted).
-__device__ inline void finish_row_to_sink(const AggArgs &a, const Slice &s, Sink &k, int slot, int fl,
+__device__ __forceinline__ void finish_row_to_sink(const AggArgs &a, const Slice &s, Sink &k, int slot, int fl,
                                           int32_t i, float di, float4 xi, float4 acc) {
   using VT = V<4>;
   VT::fma(acc, di, xi);
@@ -334,7 +366,7 @@ __device__ inline void finish_row_to_sink(const AggArgs &a, const Slice &s, Sink
 
 // Self-loop term, row scale, store.
 template <int VEC>
-__device__ inline void finish_row(const AggArgs &a, const Slice &s, int32_t i, float di,
+__device__ __forceinline__ void finish_row(const AggArgs &a, const Slice &s, int32_t i, float di,
                                   typename V<VEC>::T xi, typename V<VEC>::T acc) {
   using VT = V<VEC>;
   VT::fma(acc, di, xi);
@@ -342,8 +374,16 @@ __device__ inline void finish_row(const AggArgs &a, const Slice &s, int32_t i, f
 }
 
 template <int VEC>
-__device__ inline void reduce_slots(int ls_log2, typename V<VEC>::T &acc) {
+__device__ __forceinline__ void reduce_slots(int ls_log2, typename V<VEC>::T &acc) {
   for (int m = kWave >> 1; m >= (1 << ls_log2); m >>= 1) V<VEC>::add(acc, V<VEC>::shfl_xor(acc, m));
+}
+
+constexpr bool kPartialNt = PIPAD_PARTIAL_NT;  // non-temporal stores for the partial sums
+
+// Where partial sum `slot` (= hub unit * nclass + class) of a slice goes: all partial sums of one
+// slice are contiguous, so a phase writes and the finishing kernel reads dense memory.
+__device__ __forceinline__ float *partial_slot(const AggArgs &a, int slice, int64_t slot, int fl, int vec) {
+  return a.partial + (((int64_t)slice * a.nvp + slot) << a.ls_log2) * vec + fl * vec;
 }
 
 template <int VEC, bool FAST, int U, bool UPD>
@@ -373,8 +413,8 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
   // Row gathers in flight per lane.  Measured on MI355X (N = 1M R-MAT frame): 4 beats 2 and 8 on
   // both paths; deeper bursts only queue up in front of the L1's miss slots.  Teams of fewer
   // than 4 lanes get U = LS so that U entries per lane group still fit the 64 staged entries.
-  constexpr int UL = FAST ? U : 1;  // wave-wide teams (long rows, hub segments)
-  constexpr int US = FAST ? U : 1;  // row-wide teams (short rows)
+  constexpr int UL = FAST ? U : 1;  // wave-wide teams (hub units)
+  constexpr int US = FAST ? U : 1;  // row-wide teams (mid and short rows)
   __shared__ Staged staging[kWavesPerBlock][kWave];
   Staged *lds = staging[threadIdx.x / kWave];
   const int lane = threadIdx.x % kWave;
@@ -384,75 +424,84 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
   const int team = lane >> a.ls_log2;  // lane group index within the wave
   const int nteams = kWave >> a.ls_log2;
 
+  // Workgroups are dispatched in index order and dealt round-robin to the XCDs: the launch goes
+  // through the slices (snapshot-major) one after the other, and within a slice's class parts the
+  // class of a workgroup is its index mod 8.
   const int64_t b = blockIdx.x;
-  int slice;
-  int64_t w;
-  if (a.order == 0) {
-    slice = (int)(b % a.nslices);
-    w = b / a.nslices;
-  } else {
-    // workgroups are dispatched in index order: snapshot-major numbering makes the whole chip
-    // work on one snapshot's matrix at a time
-    const int64_t per_snapshot = a.blocks_per_slice * a.fchunks;
-    const int t = (int)(b / per_snapshot);
-    const int64_t r = b - t * per_snapshot;
-    const int fc = (int)(r % a.fchunks);
-    w = r / a.fchunks;
-    slice = fc * a.k + t;
-  }
+  const int slice_seq = (int)(b / a.blocks_per_phase);
+  int64_t w = b - slice_seq * a.blocks_per_phase;
+  const int t_seq = slice_seq / a.fchunks;
+  const int slice = (slice_seq - t_seq * a.fchunks) * a.k + t_seq;
   const Slice s = slice_setup(a, slice, fl, VEC);
   const bool ntl = a.nt & 2;
 
-  if (w < a.blocks_items) {
-    // ---- one segment of a hub row per wave
-    const int64_t item = w * kWavesPerBlock + wave;
-    if (item >= a.n_items || !(a.parts & 1)) return;
-    const int32_t i = a.item_row[item];
-    const int32_t v0 = a.item_seg[item] * a.seg, v1 = v0 + a.seg;
-    const int32_t cs = a.rowptr_c[i], lc = a.rowptr_c[i + 1] - cs;
-    const int32_t ds = s.rpd[i], ld = s.rpd[i + 1] - ds;
-    typename VT::T acc = VT::zero();
-    // positions [v0, v1) of the virtual list "common entries, then exclusive entries"
-    const int32_t c0 = min(v0, lc), c1 = min(v1, lc);
-    const int32_t d0 = min(max(v0 - lc, 0), ld), d1 = min(max(v1 - lc, 0), ld);
-    const Raw fc = fetch_entry(a.col_c, s.wc, cs + c0, c1 - c0, lane, i, ntl);
-    const Raw fd = fetch_entry(s.cd, s.wd, ds + d0, d1 - d0, lane, i, ntl);
-    walk<VEC, UL, FAST>(a.col_c, s.wc, cs + c0, c1 - c0, fc, 0, kWave, lane, team, nteams, s, a.ldx, i, ntl, lds, acc);
-    walk<VEC, UL, FAST>(s.cd, s.wd, ds + d0, d1 - d0, fd, 0, kWave, lane, team, nteams, s, a.ldx, i, ntl, lds, acc);
-    reduce_slots<VEC>(a.ls_log2, acc);
-    if (team == 0 && s.fvalid)
-      VT::store(a.partial + (((int64_t)item * a.nslices + slice) << a.ls_log2) * VEC + fl * VEC, acc, false);
-    return;
+  // ---- what this wave works on: a batch of consecutive list elements.  Class parts of hub units
+  //      (from the class-grouped copies, ending in a partial sum) and whole mid rows: the whole
+  //      wave on one list at a time, its lane groups taking different entries.  Short rows: one
+  //      lane group each, nteams side by side.  The metadata of the whole batch is loaded up front
+  //      (lane l holds element l of the batch), and while one element is being gathered the first
+  //      chunk of entries (and, for whole rows, the self-loop row) of the next one are already on
+  //      their way.
+  // (every field is read into a local before the control flow that chooses among them, so that
+  // the kernel arguments are only ever read at constant offsets)
+  const int nsub = 1 << a.sub_log2;
+  const int32_t *const p_items = a.item_row, *const p_mid = a.rows_long, *const p_short = a.rows_short;
+  const int64_t n_items = a.n_items, n_mid = a.n_long, n_short = a.n_short;
+  const int b_wide = a.batch_wide, b_mid = a.batch_mid, b_short = a.batch_short;
+  const int64_t wide_blocks = (int64_t)kClasses * a.blocks_wide;  // per sub class
+  const int64_t split_blocks = nsub * wide_blocks;
+  const bool split = w < split_blocks;                  // class parts of hub units
+  const bool wide = w < split_blocks + a.blocks_mid;    // ... or whole mid rows: a wave per list
+  int cls = 0;  // column class of this wave's class parts
+  if (split) {
+    const int sub = (int)(w / wide_blocks);  // the sub classes come one after the other in time
+    w -= sub * wide_blocks;
+    cls = ((int)(w & (kClasses - 1)) << a.sub_log2) + sub;
+    w >>= 3;
+  } else if (wide) {
+    w -= split_blocks;
+  } else {
+    w -= split_blocks + a.blocks_mid;
   }
-  w -= a.blocks_items;
-
-  // ---- rows: a wave takes a batch of consecutive rows of one list.  Long rows: the whole wave
-  //      works on one row at a time (its lane groups take different entries).  Short rows: one
-  //      lane group per row, nteams rows at a time.  The metadata of the whole batch is loaded
-  //      up front (lane l holds row l of the batch), and while one row is being gathered the
-  //      first chunk of entries and the self-loop row of the next one are already on their way.
-  const bool long_rows = w < a.blocks_long;
-  if (!long_rows) w -= a.blocks_long;
-  const int32_t *list = long_rows ? a.rows_long : a.rows_short;
-  const int64_t list_len = long_rows ? a.n_long : a.n_short;
-  const int batch = long_rows ? a.batch_long : a.batch_short;
+  const int32_t *list = split ? p_items : wide ? p_mid : p_short;
+  const int64_t list_len = split ? n_items : wide ? n_mid : n_short;
+  const int batch = split ? b_wide : wide ? b_mid : b_short;
   const int64_t first = (w * kWavesPerBlock + wave) * batch;
-  if (first >= list_len || !(a.parts & (long_rows ? 2 : 4))) return;
+  if (first >= list_len) return;
+#ifdef PIPAD_PARTS_MASK  // measurement builds only: which kinds of work items run (results incomplete)
+  if (!((PIPAD_PARTS_MASK) & (split ? 1 : wide ? 2 : 4))) return;
+#endif
   const int rows_here = (int)min((int64_t)batch, list_len - first);
+  // entry lists: the class-grouped copies for hub units, the frame's CSRs for whole rows
+  const int32_t *colc = split ? a.scol : a.col_c;
+  const float *wcs = split ? s.swc : s.wc;
+  const int32_t *cold = split ? a.scol + a.total_c : s.cd;
+  const float *wds = split ? a.swd : s.wd;
+  // hub units only: first class part in sptr == first partial sum; nclass of them per unit
+  const int64_t v_first = first * a.nclass + cls;
   int32_t r = 0, mc0 = 0, mc1 = 0, md0 = 0, md1 = 0;
   float mdi = 0.f;
   if (lane < rows_here) {
     r = list[first + lane];
-    mc0 = a.rowptr_c[r]; mc1 = a.rowptr_c[r + 1];
-    md0 = s.rpd[r]; md1 = s.rpd[r + 1];
-    mdi = s.dv[r];
+    if (split) {
+      const int64_t v = v_first + (int64_t)lane * a.nclass;
+      mc0 = (int32_t)a.sptr[v];
+      mc1 = (int32_t)a.sptr[v + 1];
+      const int64_t vd = (int64_t)(1 + s.t) * a.nv + v;
+      md0 = (int32_t)((int64_t)a.sptr[vd] - a.total_c);
+      md1 = (int32_t)((int64_t)a.sptr[vd + 1] - a.total_c);
+    } else {
+      mc0 = a.rowptr_c[r]; mc1 = a.rowptr_c[r + 1];
+      md0 = s.rpd[r]; md1 = s.rpd[r + 1];
+      mdi = s.dv[r];
+    }
   }
-  const int per_step = long_rows ? 1 : nteams;          // rows worked on side by side
-  const int team_base = long_rows ? 0 : team << a.ls_log2;
-  const int team_lanes = long_rows ? kWave : ls;
-  const int q = long_rows ? lane : fl;
-  const int slot = long_rows ? team : 0;
-  const int nslots = long_rows ? nteams : 1;
+  const int per_step = wide ? 1 : nteams;          // elements worked on side by side
+  const int team_base = wide ? 0 : team << a.ls_log2;
+  const int team_lanes = wide ? kWave : ls;
+  const int q = wide ? lane : fl;
+  const int slot = wide ? team : 0;
+  const int nslots = wide ? nteams : 1;
 
   struct Item {
     int32_t i, cs, clen, ds, dlen;
@@ -461,9 +510,9 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
     Raw fc, fd;
     typename VT::T xi;
   };
-  auto prefetch = [&](int step) {
+  auto prefetch = [&](int step) __attribute__((always_inline)) {
     Item it;
-    const int li = step * per_step + (long_rows ? 0 : team);
+    const int li = step * per_step + (wide ? 0 : team);
     it.have = li < rows_here;
     const int src = it.have ? li : 0;
     it.i = __shfl(r, src, kWave);
@@ -473,29 +522,33 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
     it.dlen = __shfl(md1, src, kWave) - it.ds;
     it.di = __shfl(mdi, src, kWave);
     if (!it.have) { it.clen = 0; it.dlen = 0; }
-    it.fc = fetch_entry(a.col_c, s.wc, it.cs, it.clen, q, it.i, ntl);
-    it.fd = fetch_entry(s.cd, s.wd, it.ds, it.dlen, q, it.i, ntl);
-    it.xi = VT::load(s.xb + (int64_t)it.i * a.ldx);
+    it.fc = fetch_entry(colc, wcs, it.cs, it.clen, q, it.i, ntl);
+    it.fd = fetch_entry(cold, wds, it.ds, it.dlen, q, it.i, ntl);
+    it.xi = VT::zero();
+    if (!split) it.xi = VT::load(s.xb + (int64_t)it.i * a.ldx);
     return it;
   };
   const int nsteps = (rows_here + per_step - 1) / per_step;
   Item nxt = prefetch(0);
   for (int step = 0; step < nsteps; ++step) {
     const Item cur = nxt;
-    const int rows_now = long_rows ? 1 : min(per_step, rows_here - step * per_step);
+    const int rows_now = wide ? 1 : min(per_step, rows_here - step * per_step);
     if constexpr (UPD) {
       // Make room in the tile before the next rows' loads are requested: the multiplication then
       // runs while nothing but this step's (already needed) data is in flight, and its registers
       // do not compete with the prefetched rows.
-      if (sink.cnt + rows_now > kTileRows) sink_flush(a, s, sink, lane);
+      if (!split && sink.cnt + rows_now > kTileRows) sink_flush(a, s, sink, lane);
     }
     if (step + 1 < nsteps) nxt = prefetch(step + 1);
     typename VT::T acc = VT::zero();
-    if (long_rows) {
-      walk<VEC, UL, FAST>(a.col_c, s.wc, cur.cs, cur.clen, cur.fc, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
-      walk<VEC, UL, FAST>(s.cd, s.wd, cur.ds, cur.dlen, cur.fd, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
+    if (wide) {
+      walk<VEC, UL, FAST>(colc, wcs, cur.cs, cur.clen, cur.fc, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
+      walk<VEC, UL, FAST>(cold, wds, cur.ds, cur.dlen, cur.fd, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
       reduce_slots<VEC>(a.ls_log2, acc);
-      if constexpr (UPD) {
+      if (split) {
+        if (team == 0 && s.fvalid)
+          VT::store(partial_slot(a, slice, v_first + (int64_t)step * a.nclass, fl, VEC), acc, kPartialNt);
+      } else if constexpr (UPD) {
         if (team == 0) finish_row_to_sink(a, s, sink, sink.cnt, fl, cur.i, cur.di, cur.xi, acc);
         sink.cnt += 1;
       } else {
@@ -503,8 +556,8 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
       }
     } else {
       if (cur.have) {
-        walk<VEC, US, FAST>(a.col_c, s.wc, cur.cs, cur.clen, cur.fc, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
-        walk<VEC, US, FAST>(s.cd, s.wd, cur.ds, cur.dlen, cur.fd, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
+        walk<VEC, US, FAST>(colc, wcs, cur.cs, cur.clen, cur.fc, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
+        walk<VEC, US, FAST>(cold, wds, cur.ds, cur.dlen, cur.fd, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
       }
       if constexpr (UPD) {
         if (cur.have) finish_row_to_sink(a, s, sink, sink.cnt + team, fl, cur.i, cur.di, cur.xi, acc);
@@ -517,8 +570,16 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
   if constexpr (UPD) sink_flush(a, s, sink, lane);
 }
 
+#ifndef PIPAD_AGG_DEPTH
+#define PIPAD_AGG_DEPTH 4  // row gathers in flight per lane on the main path
+#endif
+#ifndef PIPAD_AGG_WAVES
+#define PIPAD_AGG_WAVES 1  // lower bound on waves per SIMD the register allocation must allow
+#endif
+
 template <int VEC, bool FAST, int U>
-__global__ __launch_bounds__(kBlock) void k_aggregate(const AggArgs a) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(PIPAD_AGG_WAVES)))
+void k_aggregate(const AggArgs a) {
   aggregate_body<VEC, FAST, U, false>(a);
 }
 
@@ -529,11 +590,12 @@ void k_aggregate_update(const AggArgs a) {
   aggregate_body<4, true, 4, true>(a);
 }
 
-// Adds the partial sums of every hub row in a fixed order and finishes the row.
-// One wave per (hub row, slice); the lane teams stride over the row's segments.
-// UPD: the slice is the whole row; the few hub rows are multiplied by W with plain FMAs.
+// Adds the partial sums of every hub row in a fixed order and finishes the row.  One wave per
+// (hub row, slice), slice-major so that consecutive waves read consecutive partial sums; the lane
+// teams stride over the row's class parts.
+// UPD: the slice is the whole row; these rows are multiplied by W with plain FMAs.
 template <int VEC, bool UPD = false>
-__global__ __launch_bounds__(kBlock) void k_hub_finish(const AggArgs a) {
+__global__ __launch_bounds__(kBlock) void k_split_finish(const AggArgs a) {
   using VT = V<VEC>;
   __shared__ __align__(16) float yrow[UPD ? kWavesPerBlock : 1][UPD ? kWave : 1];
   const int lane = threadIdx.x % kWave;
@@ -542,17 +604,19 @@ __global__ __launch_bounds__(kBlock) void k_hub_finish(const AggArgs a) {
   const int fl = lane & (ls - 1);
   const int team = lane >> a.ls_log2;
   const int nteams = kWave >> a.ls_log2;
+  const int64_t row_blocks = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock;
   const int64_t b = blockIdx.x;
-  const int slice = (int)(b % a.nslices);
-  const int64_t hr = (b / a.nslices) * kWavesPerBlock + wave;
-  if (hr >= a.n_hub) return;
+  const int slice = (int)(b / row_blocks);
+  const int64_t sr = (b - slice * row_blocks) * kWavesPerBlock + wave;
+  if (sr >= a.n_hub) return;
   const Slice s = slice_setup(a, slice, fl, VEC);
-  const int32_t i = a.hub_rows[hr];
-  const int32_t it0 = a.hub_item_off[hr], it1 = a.hub_item_off[hr + 1];
+  const int32_t i = a.hub_rows[sr];
+  const int64_t v0 = (int64_t)a.hub_item_off[sr] * a.nclass;  // the row's partial sums
+  const int64_t v1 = (int64_t)a.hub_item_off[sr + 1] * a.nclass;
   typename VT::T acc = VT::zero();
   if (s.fvalid)
-    for (int32_t it = it0 + team; it < it1; it += nteams)
-      VT::add(acc, VT::load(a.partial + (((int64_t)it * a.nslices + slice) << a.ls_log2) * VEC + fl * VEC));
+    for (int64_t v = v0 + team; v < v1; v += nteams)
+      VT::add(acc, VT::load(partial_slot(a, slice, v, fl, VEC)));
   reduce_slots<VEC>(a.ls_log2, acc);
   if constexpr (UPD) {
     if (team == 0) {
@@ -751,19 +815,28 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_coalescent(const AggArgs a
   const char *xbytes = reinterpret_cast<const char *>(a.X[0]);
   const uint32_t lane_bytes = (uint32_t)lane_col * 4u;
 
-  // Adds row i's entries [c_lo, c_hi) of the overlap part and [d_lo, d_hi) of this lane's own
-  // exclusive part; positions are relative to the row start.
-  auto walk_row = [&](int32_t i, int32_t cs, int32_t c_lo, int32_t c_hi, int32_t d_lo, int32_t d_hi,
+  // Entry lists: short and mid rows are walked from the frame's CSRs, hub units from the
+  // class-grouped copies (all classes of a unit are contiguous there, so a unit is one list).
+  const int32_t *const scol_d = a.scol + a.total_c;
+  const float *const swd = a.swd;
+  const int64_t nu_nc = a.nv;  // class parts per part of the frame
+
+  // Adds `clen` overlap entries starting at col[cs] (scales scale_v[cs ...] of snapshot group
+  // member v) and this lane's own `dlen` exclusive entries starting at dcol[ds] / dw[ds].
+  auto walk_row = [&](int32_t i, bool grouped, int32_t cs, int32_t clen, int32_t ds, int32_t dlen,
                       int team_base, int team_lanes, int q, int slot, int nslots,
-                      typename VT::T &acc) {
-    for (int32_t base = c_lo; base < c_hi; base += team_lanes) {
-      const int32_t cnt = min(team_lanes, c_hi - base);
+                      typename VT::T &acc) __attribute__((always_inline)) {
+    const int32_t *colp = grouped ? a.scol : a.col_c;
+    for (int32_t base = 0; base < clen; base += team_lanes) {
+      const int32_t cnt = min(team_lanes, clen - base);
       int32_t c = i;
-      if (q < cnt) c = a.col_c[cs + base + q];
+      if (q < cnt) c = colp[cs + base + q];
       lds_off[team_base + q] = (uint32_t)c * row_bytes;
       for (int v = 0; v < sg; ++v) {
         const int tv = min(g * sg + v, a.k - 1);
-        lds_w[(team_base + q) * sg + v] = q < cnt ? a.wc[tv][cs + base + q] : 0.f;
+        const float *w_plain = a.wc[tv], *w_grouped = a.swc[tv];
+        const float *wv = grouped ? w_grouped : w_plain;
+        lds_w[(team_base + q) * sg + v] = q < cnt ? wv[cs + base + q] : 0.f;
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       if (team_lanes >= 4 * nslots) {
@@ -795,20 +868,19 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_coalescent(const AggArgs a
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
     if (valid) {
-      const int32_t ds = rpd[i];
-      const int32_t dlen = rpd[i + 1] - ds;
-      const int32_t hi = min(d_hi, dlen);
-      // four entries in flight; positions past the end read the row's first entry with weight 0
-      for (int32_t e = d_lo + slot; e < hi; e += 4 * nslots) {
+      const int32_t *dcol = grouped ? scol_d : cd;
+      const float *dw = grouped ? swd : wd;
+      // four entries in flight; positions past the end read the list's first entry with weight 0
+      for (int32_t e = slot; e < dlen; e += 4 * nslots) {
         int32_t j[4];
         float wt[4];
         typename VT::T x[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int32_t ev = e + v * nslots;
-          const bool live = ev < hi;
-          j[v] = cd[ds + (live ? ev : e)];
-          wt[v] = live ? wd[ds + ev] : 0.f;
+          const bool live = ev < dlen;
+          j[v] = dcol[ds + (live ? ev : e)];
+          wt[v] = live ? dw[ds + ev] : 0.f;
         }
 #pragma unroll
         for (int v = 0; v < 4; ++v) x[v] = VT::load(xlane + (int64_t)j[v] * a.ldx);
@@ -817,65 +889,90 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_coalescent(const AggArgs a
       }
     }
   };
-  auto finish = [&](int32_t i, typename VT::T acc) {
+  auto finish = [&](int32_t i, typename VT::T acc) __attribute__((always_inline)) {
     if (!valid) return;
     const float di = dv[i];
     VT::fma(acc, di, VT::load(xlane + (int64_t)i * a.ldx));
     VT::store(ylane + (int64_t)i * a.ldy, VT::scale(di, acc), a.nt & 1);
   };
+  // Entry lists of unit un: the overlap part (the same for all lanes) and this lane's own
+  // exclusive part.
+  auto unit_lists = [&](int64_t un, int32_t *cs, int32_t *clen, int32_t *ds, int32_t *dlen)
+      __attribute__((always_inline)) {
+    const int64_t vc = un * a.nclass;
+    const uint32_t c0 = a.sptr[vc], c1 = a.sptr[vc + a.nclass];
+    const int64_t vd = (int64_t)(1 + t) * nu_nc + vc;
+    const uint32_t d0 = a.sptr[vd], d1 = a.sptr[vd + a.nclass];
+    *cs = (int32_t)c0;
+    *clen = (int32_t)(c1 - c0);
+    *ds = (int32_t)((int64_t)d0 - a.total_c);
+    *dlen = (int32_t)(d1 - d0);
+  };
 
-  if (w < a.blocks_items) {
+  const int32_t *const p_items = a.item_row, *const p_mid = a.rows_long, *const p_short = a.rows_short;
+  const int64_t n_items = a.n_items, n_mid = a.n_long, n_short = a.n_short;
+  const int b_mid = a.batch_mid, b_short = a.batch_short;
+  if (w < a.blocks_wide) {
+    // ---- one hub unit per wave: a partial sum
     const int64_t item = w * kWavesPerBlock + wave;
-    if (item >= a.n_items || !(a.parts & 1)) return;
-    const int32_t i = a.item_row[item];
-    const int32_t v0 = a.item_seg[item] * a.seg, v1 = v0 + a.seg;
-    const int32_t cs = a.rowptr_c[i], lc = a.rowptr_c[i + 1] - cs;
+    if (item >= n_items) return;
+    const int32_t i = p_items[item];
+    int32_t cs, clen, ds, dlen;
+    unit_lists(item, &cs, &clen, &ds, &dlen);
     typename VT::T acc = VT::zero();
-    walk_row(i, cs, min(v0, lc), min(v1, lc), max(v0 - lc, 0), max(v1 - lc, 0), 0, kWave, lane, team,
-             nteams, acc);
+    walk_row(i, true, cs, clen, ds, dlen, 0, kWave, lane, team, nteams, acc);
     reduce_slots<VEC>(a.ls_log2, acc);
     if (team == 0 && valid)
       VT::store(a.partial + (((int64_t)item * a.nslices + g) << a.ls_log2) * VEC + fl * VEC, acc, false);
     return;
   }
-  w -= a.blocks_items;
-  const bool long_rows = w < a.blocks_long;
-  if (!long_rows) w -= a.blocks_long;
-  const int32_t *list = long_rows ? a.rows_long : a.rows_short;
-  const int64_t list_len = long_rows ? a.n_long : a.n_short;
-  const int batch = long_rows ? a.batch_long : a.batch_short;
+  w -= a.blocks_wide;
+  const bool long_rows = w < a.blocks_mid;
+  if (!long_rows) w -= a.blocks_mid;
+  const int32_t *list = long_rows ? p_mid : p_short;
+  const int64_t list_len = long_rows ? n_mid : n_short;
+  const int batch = long_rows ? b_mid : b_short;
   const int64_t first = (w * kWavesPerBlock + wave) * batch;
-  if (first >= list_len || !(a.parts & (long_rows ? 2 : 4))) return;
+  if (first >= list_len) return;
   const int rows_here = (int)min((int64_t)batch, list_len - first);
+  if (long_rows) {
+    // ---- mid rows: a wave per row, finished at once
+    for (int step = 0; step < rows_here; ++step) {
+      const int32_t i = list[first + step];
+      const int32_t cs = a.rowptr_c[i], ce = a.rowptr_c[i + 1];
+      const int32_t ds = rpd[i];
+      typename VT::T acc = VT::zero();
+      walk_row(i, false, cs, ce - cs, ds, rpd[i + 1] - ds, 0, kWave, lane, team, nteams, acc);
+      reduce_slots<VEC>(a.ls_log2, acc);
+      if (team == 0) finish(i, acc);
+    }
+    return;
+  }
+  // ---- short rows: a lane team per row
   int32_t r = 0, mc0 = 0, mc1 = 0;
   if (lane < rows_here) {
     r = list[first + lane];
     mc0 = a.rowptr_c[r];
     mc1 = a.rowptr_c[r + 1];
   }
-  const int per_step = long_rows ? 1 : nteams;
-  const int nsteps = (rows_here + per_step - 1) / per_step;
+  const int nsteps = (rows_here + nteams - 1) / nteams;
   for (int step = 0; step < nsteps; ++step) {
-    const int li = step * per_step + (long_rows ? 0 : team);
+    const int li = step * nteams + team;
     const bool have = li < rows_here;
     const int src = have ? li : 0;
     const int32_t i = __shfl(r, src, kWave);
     const int32_t cs = __shfl(mc0, src, kWave);
     const int32_t ce = __shfl(mc1, src, kWave);  // every lane takes part: sources must be active
-    const int32_t lc = have ? ce - cs : 0;
-    typename VT::T acc = VT::zero();
-    if (long_rows) {
-      walk_row(i, cs, 0, lc, 0, INT32_MAX, 0, kWave, lane, team, nteams, acc);
-      reduce_slots<VEC>(a.ls_log2, acc);
-      if (team == 0) finish(i, acc);
-    } else if (have) {
-      walk_row(i, cs, 0, lc, 0, INT32_MAX, team << a.ls_log2, ls, fl, 0, 1, acc);
+    if (have) {
+      typename VT::T acc = VT::zero();
+      const int32_t ds = rpd[i];
+      walk_row(i, false, cs, ce - cs, ds, rpd[i + 1] - ds, team << a.ls_log2, ls, fl, 0, 1, acc);
       finish(i, acc);
     }
   }
 }
 
-// Hub rows of the coalescent kernel: adds the partial sums of a row in a fixed order.
+// Hub rows of the coalescent kernel (one partial sum per unit): adds them in a fixed order.
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void k_hub_finish_coalescent(const AggArgs a) {
   using VT = V<VEC>;
@@ -922,53 +1019,42 @@ inline size_t update_lds_bytes(const AggArgs &a) {
 }
 
 template <int VEC>
-int launch(const AggArgs &args, hipStream_t st, bool fused_update = false) {
-  AggArgs a = args;
-  const int64_t blocks_short =
-      ((int64_t)a.n_short + a.batch_short * kWavesPerBlock - 1) / (a.batch_short * kWavesPerBlock);
-  a.blocks_per_slice = (int64_t)a.blocks_items + a.blocks_long + blocks_short;
-  const int64_t blocks = a.blocks_per_slice * a.nslices;
+int launch(const AggArgs &a, bool fast, hipStream_t st, bool fused_update = false) {
+  const int64_t blocks = a.blocks_per_phase * a.nslices;
   if (blocks >= ((int64_t)1 << 31)) return PIPAD_ERR_TOO_LARGE;
-  if (blocks > 0)
-  {
-    // the fast path needs 32-bit byte offsets into a snapshot's matrix; gathers in flight per
-    // lane x lane groups per wave must not exceed the 64 staged entries, so narrow teams get fewer
-    const bool fast = (int64_t)a.n * a.ldx * 4 < ((int64_t)1 << 32) && !options().agg_generic;
-    const dim3 grid((unsigned)blocks), block(kBlock);
-    if constexpr (VEC == 4) {
-      if (fused_update) {
-        if (!fast || a.ls_log2 < 2) return PIPAD_ERR_INVALID_ARG;  // the caller checked the shape
-        hipLaunchKernelGGL(k_aggregate_update, grid, block, update_lds_bytes(a), st, a);
-        if (a.n_hub > 0) {
-          const int64_t hb = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock * a.nslices;
-          hipLaunchKernelGGL((k_hub_finish<4, true>), dim3((unsigned)hb), dim3(kBlock), 0, st, a);
-        }
-        PIPAD_HIP(hipGetLastError());
-        return PIPAD_OK;
-      }
+  const int64_t fin = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock * a.nslices;
+  if (fin >= ((int64_t)1 << 31)) return PIPAD_ERR_TOO_LARGE;
+  const dim3 grid((unsigned)blocks), block(kBlock);
+  if constexpr (VEC == 4) {
+    if (fused_update) {
+      if (!fast || a.ls_log2 < 2) return PIPAD_ERR_INVALID_ARG;  // the caller checked the shape
+      if (blocks > 0) hipLaunchKernelGGL(k_aggregate_update, grid, block, update_lds_bytes(a), st, a);
+      if (fin > 0)
+        hipLaunchKernelGGL((k_split_finish<4, true>), dim3((unsigned)fin), dim3(kBlock), 0, st, a);
+      PIPAD_HIP(hipGetLastError());
+      return PIPAD_OK;
     }
+  }
+  // gathers in flight per lane x lane groups per wave must not exceed the 64 staged entries, so
+  // narrow teams get fewer
+  if (blocks > 0) {
     if (!fast)
       hipLaunchKernelGGL((k_aggregate<VEC, false, 1>), grid, block, 0, st, a);
     else if (a.ls_log2 >= 2)
-      hipLaunchKernelGGL((k_aggregate<VEC, true, 4>), grid, block, 0, st, a);
+      hipLaunchKernelGGL((k_aggregate<VEC, true, PIPAD_AGG_DEPTH>), grid, block, 0, st, a);
     else if (a.ls_log2 == 1)
       hipLaunchKernelGGL((k_aggregate<VEC, true, 2>), grid, block, 0, st, a);
     else
       hipLaunchKernelGGL((k_aggregate<VEC, true, 1>), grid, block, 0, st, a);
   }
-  if (a.n_hub > 0) {
-    const int64_t hb = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock * a.nslices;
-    hipLaunchKernelGGL((k_hub_finish<VEC>), dim3((unsigned)hb), dim3(kBlock), 0, st, a);
-  }
+  if (fin > 0) hipLaunchKernelGGL((k_split_finish<VEC>), dim3((unsigned)fin), dim3(kBlock), 0, st, a);
   PIPAD_HIP(hipGetLastError());
   return PIPAD_OK;
 }
 
 template <int VEC>
 int launch_coalescent(const AggArgs &a, hipStream_t st) {
-  const int64_t blocks_short =
-      ((int64_t)a.n_short + a.batch_short * kWavesPerBlock - 1) / (a.batch_short * kWavesPerBlock);
-  const int64_t blocks = ((int64_t)a.blocks_items + a.blocks_long + blocks_short) * a.nslices;
+  const int64_t blocks = ((int64_t)a.blocks_wide + a.blocks_mid + a.blocks_short) * a.nslices;
   if (blocks >= ((int64_t)1 << 31)) return PIPAD_ERR_TOO_LARGE;
   const size_t lds = (size_t)kWavesPerBlock * kWave * (1 + a.sg) * sizeof(uint32_t);
   if (blocks > 0)
@@ -1014,6 +1100,7 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
                      float *const *Y, int64_t ldy, hipStream_t st, const UpdateSpec *upd,
                      float *fixed_scratch, size_t fixed_scratch_floats) {
   if (f->n == 0) return PIPAD_OK;
+  const Options &opt = f->opt;  // as they stood when the frame was built
   AggArgs a;
   std::memset(&a, 0, sizeof(a));
   a.n = f->n;
@@ -1027,27 +1114,36 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   a.rows_short = f->rows_short;
   a.rows_long = f->rows_long;
   a.item_row = f->item_row;
-  a.item_seg = f->item_seg;
+  a.item_v0 = f->item_v0;
+  a.item_v1 = f->item_v1;
   a.hub_rows = f->hub_rows;
   a.hub_item_off = f->hub_item_off;
-  a.seg = f->hub_segment;
+  a.sptr = f->sptr;
+  a.scol = f->scol;
+  a.swd = f->swd;
+  a.total_c = f->split_total[0];
+  a.sub_log2 = f->sub_log2;
+  a.nclass = f->nclass;
+  a.nv = (int64_t)f->n_units * f->nclass;
+  a.nvp = a.nv;
   a.n_short = f->n_short;
   a.n_long = f->n_long;
   a.n_items = f->n_items;
   a.n_hub = f->n_hub;
-  a.blocks_items = (f->n_items + kWavesPerBlock - 1) / kWavesPerBlock;
-  a.nt = (int32_t)options().agg_nt;
-  a.parts = (int32_t)options().agg_parts;
+  a.nt = (int32_t)opt.agg_nt;
   bool vec4 = F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
   for (int t = 0; t < f->k; ++t) {
     a.rowptr_d[t] = f->rowptr_d[t];
     a.col_d[t] = f->col_d[t];
     a.wc[t] = f->wc[t];
     a.wd[t] = f->wd[t];
+    a.swc[t] = f->swc[t];
     a.X[t] = X[t];
     a.Y[t] = Y ? Y[t] : nullptr;
     if ((reinterpret_cast<uintptr_t>(X[t]) | reinterpret_cast<uintptr_t>(a.Y[t])) & 15u) vec4 = false;
   }
+  // the fast path needs 32-bit byte offsets into a snapshot's matrix
+  const bool fast = (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32) && !opt.agg_generic;
   // The update rides inside the aggregation kernel when a slice is a whole row of one snapshot
   // (F <= 64 in float4 pieces), W fits next to the row tiles in LDS and the fast addressing
   // applies; other shapes aggregate into Y first and multiply afterwards.
@@ -1059,15 +1155,14 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     a.ldw = upd->ldw;
     a.ldh = upd->ldh;
     for (int t = 0; t < f->k; ++t) a.H[t] = upd->H[t];
-    fused = vec4 && F >= 16 && F <= 64 && upd->Fo >= 16 && upd->Fo <= 64 && upd->Fo % 16 == 0 &&
-            (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32) && !options().agg_generic;
+    fused = vec4 && F >= 16 && F <= 64 && upd->Fo >= 16 && upd->Fo <= 64 && upd->Fo % 16 == 0 && fast;
     if (!fused && !Y) return PIPAD_ERR_INVALID_ARG;  // the two-step form needs Y as its workspace
   }
   // Small F handed over as one concatenated operand: the coalescent kernel (snapshot groups).
   // Measured on every benchmark graph at F = 2, 6, 16: on that operand it beats the per-snapshot
   // slices by 1.2-2.5x (a slice would use 4*F bytes of every k*F-float row it touches, and all
   // XCDs would fetch the same lines); only operands of a few hundred KB are a tie.
-  const int64_t mode = options().agg_coalescent;  // 0 never, 1 automatic, 2 whenever possible
+  const int64_t mode = opt.agg_coalescent;  // 0 never, 1 automatic, 2 whenever possible
   const bool wanted = mode >= 2 || (mode == 1 && (int64_t)f->n * f->k * F * 4 >= ((int64_t)1 << 20));
   bool coalescent = wanted && !upd && F < 32 && f->k > 1 && ldx >= (int64_t)f->k * F &&
                     ldy >= (int64_t)f->k * F && (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32);
@@ -1083,25 +1178,11 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     a.fchunks = 1;
     a.nslices = (f->k + a.sg - 1) / a.sg;                   // snapshot groups
   }
-  // slice geometry: LS lanes of VEC columns each, at most 64 columns per slice
+  // slice geometry: LS lanes of VEC columns each, at most 64 columns per slice (a gathered piece
+  // of a row is then at most 256 bytes: two cache lines)
   const int vec = coalescent ? cvec : vec4 ? 4 : 1;
-  // With fewer than 8 snapshots a 64-column slice would leave XCDs sharing a slice (and their
-  // L2s caching the same rows twice); 32 columns -- still a whole 128-byte line per gathered row --
-  // doubles the number of slices.
   int max_cols = 64;
-  if (options().slice_cols > 0) max_cols = (int)std::min<int64_t>(64, options().slice_cols);
-  else if ((int64_t)f->k * ((F + 63) / 64) < 8 && F > 32 && !fused) max_cols = 32;
-  // Order of the slices in time.  Side by side (every XCD on its own snapshot) or one snapshot
-  // after the other (the whole chip on one matrix, in 32-column slices: an XCD's L2 then holds
-  // twice as many - half as wide - hot rows, and the memory-side cache sees one matrix at a time).
-  // Measured: the second wins by 4-19 % for rows of more than 64 columns and for 64-column
-  // matrices of 64 MB and more per snapshot, is level on a 51 MB matrix of 64 columns, and loses
-  // up to 25 % at 32 columns and fewer (one slice per snapshot: nothing to narrow).
-  a.order = (int32_t)options().agg_order;
-  if (a.order >= 2)
-    a.order = (F > 64 || (F > 32 && (int64_t)f->n * F * 4 >= ((int64_t)64 << 20))) ? 1 : 0;
-  if (a.order == 1 && options().slice_cols == 0 && F > 32) max_cols = 32;
-  if (fused) max_cols = 64;
+  if (opt.slice_cols > 0 && !fused) max_cols = (int)std::min<int64_t>(64, opt.slice_cols);
   const int cols = std::min(F, max_cols);
   if (!coalescent) {
     a.ls_log2 = ceil_log2((cols + vec - 1) / vec);
@@ -1109,43 +1190,70 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
     a.nslices = f->k * a.fchunks;
   }
   const int sw = (1 << a.ls_log2) * vec;
+  const int nteams = kWave >> a.ls_log2;
 
   // Rows per wave: the full batches amortise the per-wave set-up on big frames; a small frame gets
-  // shorter ones (down to one row per lane team / per wave), until the launch has a few waves for
-  // every slot of the chip or the batches cannot shrink further.
+  // shorter ones (down to one step per wave), until what runs together -- one slice, or all
+  // snapshot groups of the coalescent kernel -- has a few waves for every slot of the chip or the
+  // batches cannot shrink further.
   {
-    const int nteams = kWave >> a.ls_log2;
     const int64_t enough = 4 * 8192;  // waves
     a.batch_short = kShortRowsPerWave;
-    a.batch_long = kLongRowsPerWave;
-    // (one snapshot after the other: what runs together is one snapshot's slices)
-    const int together = a.order == 1 && !coalescent ? a.fchunks : a.nslices;
+    a.batch_mid = kLongRowsPerWave;
+    a.batch_wide = coalescent ? 1 : kWideUnitsPerWave;
+    const int min_mid = 1;
+    const int64_t mult = coalescent ? a.nslices : 1;
+    const int64_t mult_wide = coalescent ? a.nslices : f->nclass;
     auto waves = [&]() {
-      return ((int64_t)(f->n_short + a.batch_short - 1) / a.batch_short +
-              (int64_t)(f->n_long + a.batch_long - 1) / a.batch_long + f->n_items) * together;
+      return (int64_t)(f->n_short + a.batch_short - 1) / a.batch_short * (coalescent ? a.nslices : 1) +
+             (int64_t)(f->n_long + a.batch_mid - 1) / a.batch_mid * mult +
+             (int64_t)(f->n_items + a.batch_wide - 1) / a.batch_wide * mult_wide;
     };
-    while (waves() < enough && (a.batch_short > nteams || a.batch_long > 1)) {
+    while (waves() < enough &&
+           (a.batch_short > nteams || a.batch_mid > min_mid || a.batch_wide > 1)) {
       if (a.batch_short > nteams) a.batch_short >>= 1;
-      if (a.batch_long > 1) a.batch_long >>= 1;
+      if (a.batch_mid > min_mid) a.batch_mid >>= 1;
+      if (a.batch_wide > 1) a.batch_wide >>= 1;
     }
     a.batch_short = std::max(a.batch_short, nteams);
-    a.blocks_long = (f->n_long + kWavesPerBlock * a.batch_long - 1) / (kWavesPerBlock * a.batch_long);
+    a.batch_mid = std::max(a.batch_mid, min_mid);
+    auto blocks_for = [](int64_t items, int per_wave) {
+      return (int32_t)((items + (int64_t)kWavesPerBlock * per_wave - 1) / ((int64_t)kWavesPerBlock * per_wave));
+    };
+    a.blocks_wide = blocks_for(f->n_items, a.batch_wide);
+    a.blocks_mid = blocks_for(f->n_long, a.batch_mid);
+    a.blocks_short = blocks_for(f->n_short, a.batch_short);
+    if (!coalescent) {
+      // phases start at multiples of 8 workgroups
+      a.blocks_short += (kClasses - (a.blocks_mid + a.blocks_short) % kClasses) % kClasses;
+      a.blocks_per_phase = ((int64_t)kClasses * a.blocks_wide << f->sub_log2) + a.blocks_mid + a.blocks_short;
+    }
   }
 
-  // scratch for the partial sums of hub segments: n_items x nslices x slice width
-  const size_t need = (size_t)f->n_items * (size_t)a.nslices * (size_t)sw;
+  // scratch for the partial sums: one slice-wide vector per class part (per hub unit for the
+  // coalescent kernel) and slice
+  const size_t need = (coalescent ? (size_t)f->n_items : (size_t)a.nvp) * (size_t)a.nslices * (size_t)sw;
   if (fixed_scratch) {
     if (need > fixed_scratch_floats) return PIPAD_ERR_SCRATCH;
   } else if (need > f->partial_floats) {
+    // growing means allocating: not while the stream is being captured into a graph
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &capturing) != hipSuccess) {
+      (void)hipGetLastError();
+    } else if (capturing != hipStreamCaptureStatusNone) {
+      return PIPAD_ERR_SCRATCH;
+    }
     void *ptr = nullptr;
     if (f->alloc) {
       // the caller's allocator owns the memory; a smaller buffer from before stays with it
       ptr = f->alloc(need * sizeof(float), f->alloc_ctx);
       if (!ptr) return PIPAD_ERR_ALLOC;
     } else {
-      // the old buffer may still be in use by earlier work on another stream of the caller
-      PIPAD_HIP(hipDeviceSynchronize());
-      if (f->partial) (void)hipFree(f->partial);
+      // the old buffer may still be in use by earlier aggregations of this frame
+      if (f->partial) {
+        PIPAD_HIP(hipDeviceSynchronize());
+        (void)hipFree(f->partial);
+      }
       f->partial = nullptr;
       f->partial_floats = 0;
       if (hipMalloc(&ptr, need * sizeof(float)) != hipSuccess) {
@@ -1160,8 +1268,8 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   if (coalescent)
     return cvec == 4 ? launch_coalescent<4>(a, st)
                      : cvec == 2 ? launch_coalescent<2>(a, st) : launch_coalescent<1>(a, st);
-  if (fused) return launch<4>(a, st, true);
-  const int rc = vec4 ? launch<4>(a, st) : launch<1>(a, st);
+  if (fused) return launch<4>(a, fast, st, true);
+  const int rc = vec4 ? launch<4>(a, fast, st) : launch<1>(a, fast, st);
   if (rc != PIPAD_OK || !upd) return rc;
   const int64_t tiles = ((int64_t)f->n + 15) / 16 * f->k;
   // weights resident in LDS when a column block of them fits (40 KB, tiles on top: under 64 KB), else straight from memory

@@ -175,30 +175,37 @@ const char *pipad_strerror(int status) {
 
 const char *pipad_last_hip_error(void) { return pipad::g_hip_error.c_str(); }
 
-static int64_t *option_slot(const char *key) {
+static int64_t *option_slot(const char *key, int64_t *max_value) {
   pipad::Options &o = pipad::options();
   if (!key) return nullptr;
-  if (!std::strcmp(key, "short_max")) return &o.short_max;
-  if (!std::strcmp(key, "agg_nt")) return &o.agg_nt;
-  if (!std::strcmp(key, "agg_parts")) return &o.agg_parts;
-  if (!std::strcmp(key, "agg_generic")) return &o.agg_generic;
-  if (!std::strcmp(key, "slice_cols")) return &o.slice_cols;
-  if (!std::strcmp(key, "agg_order")) return &o.agg_order;
-  if (!std::strcmp(key, "agg_coalescent")) return &o.agg_coalescent;
-  if (!std::strcmp(key, "hub_threshold")) return &o.hub_threshold;
-  if (!std::strcmp(key, "hub_segment")) return &o.hub_segment;
+  const int64_t len_max = (int64_t)1 << 30;  // thresholds on row lengths
+  struct Slot { const char *name; int64_t *value; int64_t max; };
+  const Slot slots[] = {
+      {"short_max", &o.short_max, len_max},     {"mid_max", &o.mid_max, len_max},
+      {"hub_threshold", &o.hub_threshold, len_max}, {"hub_segment", &o.hub_segment, len_max},
+      {"sub_classes", &o.sub_classes, 4},
+      {"agg_nt", &o.agg_nt, 3},                 {"agg_generic", &o.agg_generic, 1},
+      {"slice_cols", &o.slice_cols, 64},        {"agg_coalescent", &o.agg_coalescent, 2},
+  };
+  for (const Slot &sl : slots)
+    if (!std::strcmp(key, sl.name)) {
+      *max_value = sl.max;
+      return sl.value;
+    }
   return nullptr;
 }
 
 int pipad_set_option(const char *key, int64_t value) {
-  int64_t *slot = option_slot(key);
-  if (!slot || value < 0) return PIPAD_ERR_INVALID_ARG;
+  int64_t max_value = 0;
+  int64_t *slot = option_slot(key, &max_value);
+  if (!slot || value < 0 || value > max_value) return PIPAD_ERR_INVALID_ARG;
   *slot = value;
   return PIPAD_OK;
 }
 
 int pipad_get_option(const char *key, int64_t *value) {
-  int64_t *slot = option_slot(key);
+  int64_t max_value = 0;
+  int64_t *slot = option_slot(key, &max_value);
   if (!slot || !value) return PIPAD_ERR_INVALID_ARG;
   *value = *slot;
   return PIPAD_OK;

@@ -452,49 +452,73 @@ __global__ __launch_bounds__(kBlock) void k_rowptr(Snaps s, Parts p, const uint3
   p.rowptr_out[part][i] = (int32_t)v;
 }
 
-// ---- per-row metadata: D^-1/2, length classes ---------------------------------------------------
+// ---- per-row metadata: D^-1/2 ------------------------------------------------------------------
 // dinv_t[i] = (1 + |row i of snapshot t|)^-1/2, evaluated in double and rounded once.
-// Length L(i) = common + longest exclusive row decides the class (see pipad_frame): the three
-// arrays written here are turned into list positions by exclusive prefix sums.
-__global__ __launch_bounds__(kBlock) void k_rowmeta(Snaps s, Parts p, int32_t n, int32_t k,
-                                                     float *dinv, float *dinv_nk,
-                                                     uint32_t *shortflag,
-                                                     uint32_t *hubflag, uint32_t *nseg,
-                                                     int32_t short_max, int32_t threshold,
-                                                     int32_t segment) {
+__global__ __launch_bounds__(kBlock) void k_dinv(Snaps s, int32_t n, int32_t k, float *dinv,
+                                                  float *dinv_nk) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i > n) return;
-  if (i == n) {  // trailing entries of the arrays that get scanned
-    shortflag[n] = 0;
-    hubflag[n] = 0;
-    nseg[n] = 0;
-    return;
-  }
-  const int32_t lc = p.rowptr_out[0][i + 1] - p.rowptr_out[0][i];
-  int32_t ldmax = 0;
+  if (i >= n) return;
   for (int t = 0; t < k; ++t) {
     const int32_t len = s.rowptr[t][i + 1] - s.rowptr[t][i];
     const float v = (float)(1.0 / sqrt((double)(len + 1)));
     dinv[(int64_t)t * n + i] = v;
     dinv_nk[i * k + t] = v;  // node-major copy for the scatter step (one line per node)
-    ldmax = max(ldmax, len - lc);
   }
-  const int64_t total = (int64_t)lc + ldmax;
-  const bool hub = total > threshold;
-  shortflag[i] = total <= short_max ? 1u : 0u;
-  hubflag[i] = hub ? 1u : 0u;
-  nseg[i] = hub ? (uint32_t)((total + segment - 1) / segment) : 0u;
 }
 
-// Turns the scanned class arrays into the row lists and the (row, segment) work items.
-// Every row is in exactly one class, so its position in the long list is i - (#short before i)
-// - (#hub before i).
+// ---- row classes --------------------------------------------------------------------------------
+// Length L(i) = common + longest exclusive row decides the class (see pipad_frame); the three
+// arrays written here are turned into list positions by exclusive prefix sums.  split_total[p]
+// receives the number of entries that the hub rows hold in part p (0 = common, 1 + t = exclusive
+// part of snapshot t): the sizes of the class-grouped copies.  Integer atomics, one per
+// workgroup and part, so the result does not depend on scheduling.
+struct PartRows {
+  const int32_t *rowptr[PIPAD_MAX_K + 1];  // common, then the k exclusive parts
+};
+
+__global__ __launch_bounds__(kBlock) void k_classify(PartRows p, int32_t n, int32_t k,
+                                                      uint32_t *shortflag, uint32_t *hubflag,
+                                                      uint32_t *nseg, uint32_t *split_total,
+                                                      int32_t short_max, int32_t mid_max,
+                                                      int32_t threshold, int32_t segment) {
+  __shared__ uint32_t sums[PIPAD_MAX_K + 1];
+  for (int q = threadIdx.x; q <= k; q += kBlock) sums[q] = 0;
+  __syncthreads();
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i == n) {  // trailing entries of the arrays that get scanned
+    shortflag[n] = 0;
+    hubflag[n] = 0;
+    nseg[n] = 0;
+  } else if (i < n) {
+    const int32_t lc = p.rowptr[0][i + 1] - p.rowptr[0][i];
+    int32_t ldmax = 0;
+    for (int q = 1; q <= k; ++q) ldmax = max(ldmax, p.rowptr[q][i + 1] - p.rowptr[q][i]);
+    const int64_t total = (int64_t)lc + ldmax;
+    const int cls = row_class(total, short_max, mid_max);
+    shortflag[i] = cls == 0 ? 1u : 0u;
+    hubflag[i] = cls == 2 ? 1u : 0u;
+    nseg[i] = cls == 2 ? hub_units(total, threshold, segment) : 0u;
+    if (cls == 2)
+      for (int q = 0; q <= k; ++q) {  // (the few split rows read their row pointers a second time)
+        const int32_t len = p.rowptr[q][i + 1] - p.rowptr[q][i];
+        if (len) atomicAdd(&sums[q], (uint32_t)len);
+      }
+  }
+  __syncthreads();
+  for (int q = threadIdx.x; q <= k; q += kBlock)
+    if (sums[q]) atomicAdd(&split_total[q], sums[q]);
+}
+
+// Turns the scanned class arrays into the row lists and the hub units.
+// Every row is in exactly one class, so its position in the mid list is i - (#short before i)
+// - (#hub before i).  A hub row that is not cut is one unit covering its whole entry list.
 __global__ __launch_bounds__(kBlock) void k_row_lists(int32_t n, const uint32_t *shortidx,
                                                        const uint32_t *hubidx,
-                                                       const uint32_t *segoff, int32_t *rows_short,
-                                                       int32_t *rows_long, int32_t *hub_rows,
-                                                       int32_t *hub_item_off, int32_t *item_row,
-                                                       int32_t *item_seg) {
+                                                       const uint32_t *segoff, int32_t segment,
+                                                       int32_t *rows_short, int32_t *rows_long,
+                                                       int32_t *hub_rows, int32_t *hub_item_off,
+                                                       int32_t *item_row, int32_t *item_v0,
+                                                       int32_t *item_v1) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i > n) return;
   if (i == n) {
@@ -510,10 +534,163 @@ __global__ __launch_bounds__(kBlock) void k_row_lists(int32_t n, const uint32_t 
     hub_item_off[hi] = (int32_t)first;
     for (uint32_t q = first; q < last; ++q) {
       item_row[q] = (int32_t)i;
-      item_seg[q] = (int32_t)(q - first);
+      const int64_t v0 = (int64_t)(q - first) * segment;
+      item_v0[q] = last - first == 1 ? 0 : (int32_t)v0;
+      item_v1[q] = last - first == 1 ? INT32_MAX : (int32_t)min(v0 + segment, (int64_t)INT32_MAX);
     }
   } else {
     rows_long[(uint32_t)i - si - hi] = (int32_t)i;
+  }
+}
+
+// ---- class-grouped copies of the split rows' entries ----------------------------------------------
+struct SplitArgs {
+  int32_t n, n_units, k;
+  int32_t sub_log2;
+  int32_t team_log2;                       // delta fill: lanes per (unit, snapshot) team
+  const int32_t *item_row, *item_v0, *item_v1;
+  const int32_t *rowptr[PIPAD_MAX_K + 1];  // parts: common, then exclusive
+  const int32_t *col[PIPAD_MAX_K + 1];
+  const float *wc[PIPAD_MAX_K];            // canonical scales of the overlap part
+  const float *wd[PIPAD_MAX_K];            // and of the exclusive parts
+  uint32_t *ulen;                          // [(k + 1) * n_units + 1]: lengths, then (scanned) starts
+  uint32_t *sptr;
+  int32_t *scol;
+  float *swc[PIPAD_MAX_K];
+  float *swd;
+  uint32_t total_c;
+};
+
+// Entries [*a, *b) of part p's column array that unit u covers.
+__device__ inline void unit_range(const SplitArgs &g, int p, int32_t u, int32_t *a, int32_t *b) {
+  const int32_t row = g.item_row[u], v0 = g.item_v0[u], v1 = g.item_v1[u];
+  const int32_t cs = g.rowptr[0][row], lc = g.rowptr[0][row + 1] - cs;
+  if (p == 0) {
+    *a = cs + min(v0, lc);
+    *b = cs + min(v1, lc);
+  } else {
+    const int32_t ds = g.rowptr[p][row], ld = g.rowptr[p][row + 1] - ds;
+    *a = ds + min(max(v0 - lc, 0), ld);
+    *b = ds + min(max(v1 - lc, 0), ld);
+  }
+}
+
+// ulen[p * n_units + u] = entries of unit u in part p (the trailing word is cleared).
+__global__ __launch_bounds__(kBlock) void k_unit_len(SplitArgs g) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t m = (int64_t)(g.k + 1) * g.n_units;
+  if (e > m) return;
+  if (e == m) { g.ulen[m] = 0; return; }
+  const int p = (int)(e / g.n_units);
+  int32_t a, b;
+  unit_range(g, p, (int32_t)(e - (int64_t)p * g.n_units), &a, &b);
+  g.ulen[e] = (uint32_t)(b - a);
+}
+
+// The class-grouped copy of one part of one unit by a team of TL = 1 << tl_log2 lanes (all of
+// them active and in step; lanes below `lane0` belong to other teams).  First pass: entries per
+// class; second pass: a stable scatter - a ballot per class gives every lane its rank among the
+// team's lanes of that class - which takes the entries' column scales along.
+template <int NC>
+__device__ inline void split_fill_part(const SplitArgs &g, int p, int32_t u, int tl_log2, int lane) {
+  const int tl = 1 << tl_log2;
+  const int q = lane & (tl - 1);      // lane within the team
+  const int lane0 = lane - q;
+  const uint64_t team_mask = (tl == kWave ? ~0ull : ((1ull << tl) - 1ull)) << lane0;
+  int32_t a, b;
+  unit_range(g, p, u, &a, &b);
+  const int32_t *col = g.col[p];
+  constexpr int UN = 4;  // chunks in flight per pass
+  uint32_t cnt[NC];
+#pragma unroll
+  for (int x = 0; x < NC; ++x) cnt[x] = 0;
+  for (int32_t e0 = a + q; e0 < b; e0 += UN * tl) {
+    int32_t cv[UN];
+#pragma unroll
+    for (int j = 0; j < UN; ++j) cv[j] = e0 + j * tl < b ? col[e0 + j * tl] : -1;
+#pragma unroll
+    for (int j = 0; j < UN; ++j) {
+      const uint32_t c = cv[j] >= 0 ? column_class(cv[j], g.sub_log2) : (uint32_t)NC;
+#pragma unroll
+      for (int x = 0; x < NC; ++x) cnt[x] += c == (uint32_t)x ? 1u : 0u;
+    }
+  }
+  uint32_t run[NC];  // next free position of every class (the same in all lanes of the team)
+  uint32_t next = g.ulen[(int64_t)p * g.n_units + u];
+  const int64_t v = ((int64_t)p * g.n_units + u) * NC;
+#pragma unroll
+  for (int x = 0; x < NC; ++x) {
+    uint32_t c = cnt[x];
+    for (int m = tl >> 1; m >= 1; m >>= 1) c += __shfl_xor(c, m, kWave);
+    run[x] = next;
+    if (q == 0) g.sptr[v + x] = next;
+    next += c;
+  }
+  const float *wd_t = g.wd[p > 0 ? p - 1 : 0];
+  for (int32_t base = a; base < b; base += UN * tl) {
+    int32_t cv[UN];
+    uint32_t pos[UN];
+#pragma unroll
+    for (int j = 0; j < UN; ++j) {
+      const int32_t e = base + j * tl + q;
+      cv[j] = e < b ? col[e] : -1;
+    }
+#pragma unroll
+    for (int j = 0; j < UN; ++j) {
+      const uint32_t cl = cv[j] >= 0 ? column_class(cv[j], g.sub_log2) : (uint32_t)NC;
+      pos[j] = 0;
+#pragma unroll
+      for (int x = 0; x < NC; ++x) {
+        const uint64_t mask = __ballot(cl == (uint32_t)x) & team_mask;
+        if (cl == (uint32_t)x) pos[j] = run[x] + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+        run[x] += (uint32_t)__popcll(mask);
+      }
+    }
+    if (p == 0) {
+      // the scales of 8 snapshots at a time: all loads go out before the first store
+      for (int t0 = 0; t0 < g.k; t0 += 8) {
+        float wv[8][UN];
+#pragma unroll
+        for (int tt = 0; tt < 8; ++tt)
+#pragma unroll
+          for (int j = 0; j < UN; ++j)
+            wv[tt][j] = (t0 + tt < g.k && cv[j] >= 0) ? g.wc[t0 + tt][base + j * tl + q] : 0.f;
+#pragma unroll
+        for (int tt = 0; tt < 8; ++tt)
+#pragma unroll
+          for (int j = 0; j < UN; ++j)
+            if (t0 + tt < g.k && cv[j] >= 0) g.swc[t0 + tt][pos[j]] = wv[tt][j];
+      }
+    } else {
+      float wv[UN];
+#pragma unroll
+      for (int j = 0; j < UN; ++j) wv[j] = cv[j] >= 0 ? wd_t[base + j * tl + q] : 0.f;
+#pragma unroll
+      for (int j = 0; j < UN; ++j)
+        if (cv[j] >= 0) g.swd[pos[j] - g.total_c] = wv[j];
+    }
+#pragma unroll
+    for (int j = 0; j < UN; ++j)
+      if (cv[j] >= 0) g.scol[pos[j]] = cv[j];
+  }
+}
+
+// One wave per unit: first the overlap part with the whole wave, then the k exclusive parts side
+// by side, a team of 64 / (k rounded up to a power of two) lanes per snapshot (the exclusive parts
+// of a unit are short where the overlap is large, and where it is small there are k of them to
+// keep the wave busy).
+template <int NC>
+__global__ __launch_bounds__(kBlock) void k_split_fill(SplitArgs g) {
+  const int lane = threadIdx.x % kWave;
+  const int64_t id = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  if (id == 0 && lane == 0)
+    g.sptr[(int64_t)(g.k + 1) * g.n_units * NC] = g.ulen[(int64_t)(g.k + 1) * g.n_units];
+  if (id >= g.n_units) return;
+  const int32_t u = __builtin_amdgcn_readfirstlane((int32_t)id);
+  split_fill_part<NC>(g, 0, u, 6, lane);
+  for (int t0 = 0; t0 < g.k; t0 += kWave >> g.team_log2) {
+    const int t = t0 + (lane >> g.team_log2);
+    if (t < g.k) split_fill_part<NC>(g, 1 + t, u, g.team_log2, lane);
   }
 }
 
@@ -521,9 +698,10 @@ __global__ __launch_bounds__(kBlock) void k_row_lists(int32_t n, const uint32_t 
 // Every selected entry is written to prefix[word] + (selected entries below it in its word), which
 // keeps the ascending column order of the input.  Besides the column index, the column scale
 // dinv_t[column] of the entry is stored: for a common entry once per snapshot, for an exclusive
-// entry for its own snapshot.  dinv_nk is [n][k] (one line per node).
+// entry for its own snapshot (dinv of one snapshot is 4 bytes per node: cache-resident).
 //
-// Common part: one lane per stored entry of snapshot 0 (most of them are selected).
+// Common part: one lane per stored entry of snapshot 0 (most of them are selected); the entry's k
+// column scales come from the node-major copy of D^-1/2 (one line per node).
 // KV > 0: k == 4 * KV, a node's k scales are read as KV 16-byte pieces; KV == 0: any k, one by one.
 template <int KV>
 __global__ __launch_bounds__(kBlock) void k_scatter_common(Snaps s, Parts p, const uint32_t *pre,
@@ -597,12 +775,13 @@ __global__ __launch_bounds__(kBlock) void k_scatter_delta_dense(Snaps s, Parts p
 
 // Collects the data-dependent sizes into one small buffer for a single copy to the host:
 // out[0 .. k+1] = prefix at the start of every part (and the end of the last), then the numbers
-// of hub rows, hub segments and short rows.
+// of hub rows, hub units and short rows, then the k + 1 split totals.
 __global__ void k_totals(Parts p, const uint32_t *pre, int32_t k, int32_t n,
                          const uint32_t *hubidx, const uint32_t *segoff,
-                         const uint32_t *shortidx, uint32_t *out) {
+                         const uint32_t *shortidx, const uint32_t *split_total, uint32_t *out) {
   const int q = threadIdx.x;
   if (q <= k + 1) out[q] = pre[p.word_off[q]];
+  if (q <= k) out[k + 5 + q] = split_total[q];
   if (q == 0) {
     out[k + 2] = hubidx[n];
     out[k + 3] = segoff[n];
@@ -618,11 +797,112 @@ int scan_exclusive(uint32_t *const *data, int count, uint32_t m, uint32_t *bsum,
 
 size_t scan_block_words(uint32_t m) { return ((size_t)m + kScanTile - 1) / kScanTile; }
 
+void frame_take_options(pipad_frame *f) {
+  const int64_t lim = (int64_t)1 << 30;  // thresholds beyond any int32 row length mean "never"
+  f->opt = options();
+  f->short_max = (int32_t)std::clamp<int64_t>(f->opt.short_max, 0, lim);
+  f->mid_max = (int32_t)std::clamp<int64_t>(f->opt.mid_max, f->short_max, lim);
+  f->hub_threshold = (int32_t)std::clamp<int64_t>(f->opt.hub_threshold, 1, lim);
+  f->hub_segment = (int32_t)std::clamp<int64_t>(f->opt.hub_segment, 1, lim);
+  f->sub_log2 = f->opt.sub_classes >= 4 ? 2 : f->opt.sub_classes >= 2 ? 1 : 0;
+  f->nclass = kClasses << f->sub_log2;
+}
+
+int launch_classify(const pipad_frame *f, uint32_t *shortflag, uint32_t *hubflag, uint32_t *nseg,
+                    uint32_t *split_total, hipStream_t st) {
+  PartRows p;
+  std::memset(&p, 0, sizeof(p));
+  p.rowptr[0] = f->rowptr_c;
+  for (int t = 0; t < f->k; ++t) p.rowptr[1 + t] = f->rowptr_d[t];
+  PIPAD_HIP(hipMemsetAsync(split_total, 0, sizeof(uint32_t) * (size_t)(f->k + 1), st));
+  hipLaunchKernelGGL(k_classify, grid1((int64_t)f->n + 1, kBlock), dim3(kBlock), 0, st, p, f->n, f->k,
+                     shortflag, hubflag, nseg, split_total, f->short_max, f->mid_max,
+                     f->hub_threshold, f->hub_segment);
+  PIPAD_HIP(hipGetLastError());
+  return PIPAD_OK;
+}
+
 void launch_row_lists(int32_t n, const uint32_t *shortidx, const uint32_t *hubidx,
                       const uint32_t *segoff, pipad_frame *f, hipStream_t st) {
   hipLaunchKernelGGL(k_row_lists, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, n, shortidx,
-                     hubidx, segoff, f->rows_short, f->rows_long, f->hub_rows, f->hub_item_off,
-                     f->item_row, f->item_seg);
+                     hubidx, segoff, f->hub_segment, f->rows_short, f->rows_long, f->hub_rows,
+                     f->hub_item_off, f->item_row, f->item_v0, f->item_v1);
+}
+
+int set_list_sizes(pipad_frame *f, uint32_t n_hub, uint32_t n_items, uint32_t n_short,
+                   const uint32_t *split_total) {
+  f->n_hub = (int32_t)n_hub;
+  f->n_items = (int32_t)n_items;
+  f->n_short = (int32_t)n_short;
+  f->n_long = f->n - f->n_short - f->n_hub;
+  f->n_units = f->n_items;
+  f->split_all = 0;
+  for (int q = 0; q <= f->k; ++q) {
+    f->split_total[q] = split_total[q];
+    f->split_all += split_total[q];
+  }
+  if (f->split_all >= ((int64_t)1 << 31) ||
+      (int64_t)(f->k + 1) * f->n_units * f->nclass >= ((int64_t)1 << 31))
+    return PIPAD_ERR_TOO_LARGE;
+  return PIPAD_OK;
+}
+
+void want_lists(Arena &a, pipad_frame *f, uint32_t **ulen, uint32_t **ubsum) {
+  a.want(&f->rows_short, (size_t)f->n_short);
+  a.want(&f->rows_long, (size_t)f->n_long);
+  a.want(&f->hub_rows, (size_t)f->n_hub);
+  a.want(&f->hub_item_off, (size_t)f->n_hub + 1);
+  a.want(&f->item_row, (size_t)f->n_items);
+  a.want(&f->item_v0, (size_t)f->n_items);
+  a.want(&f->item_v1, (size_t)f->n_items);
+  const size_t nu = (size_t)(f->k + 1) * f->n_units;
+  a.want(&f->sptr, nu * f->nclass + 1);
+  a.want(&f->scol, (size_t)f->split_all);
+  for (int t = 0; t < f->k; ++t) a.want(&f->swc[t], (size_t)f->split_total[0]);
+  a.want(&f->swd, (size_t)(f->split_all - f->split_total[0]));
+  a.want(ulen, nu + 1);
+  a.want(ubsum, scan_block_words((uint32_t)(nu + 1)) + 1);
+}
+
+int build_split_arrays(pipad_frame *f, uint32_t *ulen, uint32_t *bsum, hipStream_t st) {
+  if (f->n_units == 0) return PIPAD_OK;
+  SplitArgs g;
+  std::memset(&g, 0, sizeof(g));
+  g.n = f->n;
+  g.n_units = f->n_units;
+  g.k = f->k;
+  g.sub_log2 = f->sub_log2;
+  g.team_log2 = 6;
+  while (g.team_log2 > 0 && (kWave >> g.team_log2) < f->k) --g.team_log2;  // 64 / team lanes >= k
+  g.item_row = f->item_row;
+  g.item_v0 = f->item_v0;
+  g.item_v1 = f->item_v1;
+  g.rowptr[0] = f->rowptr_c;
+  g.col[0] = f->col_c;
+  for (int t = 0; t < f->k; ++t) {
+    g.rowptr[1 + t] = f->rowptr_d[t];
+    g.col[1 + t] = f->col_d[t];
+    g.wc[t] = f->wc[t];
+    g.wd[t] = f->wd[t];
+    g.swc[t] = f->swc[t];
+  }
+  g.ulen = ulen;
+  g.sptr = f->sptr;
+  g.scol = f->scol;
+  g.swd = f->swd;
+  g.total_c = (uint32_t)f->split_total[0];
+  const int64_t nu = (int64_t)(f->k + 1) * f->n_units;
+  hipLaunchKernelGGL(k_unit_len, grid1(nu + 1, kBlock), dim3(kBlock), 0, st, g);
+  PIPAD_HIP(hipGetLastError());
+  {
+    uint32_t *one = ulen;
+    const int rc = exclusive_scan(&one, 1, (uint32_t)(nu + 1), bsum, st);
+    if (rc != PIPAD_OK) return rc;
+  }
+  auto fill = f->sub_log2 == 0 ? k_split_fill<8> : f->sub_log2 == 1 ? k_split_fill<16> : k_split_fill<32>;
+  hipLaunchKernelGGL(fill, grid1(f->n_units, kWavesPerBlock), dim3(kBlock), 0, st, g);
+  PIPAD_HIP(hipGetLastError());
+  return PIPAD_OK;
 }
 
 int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags,
@@ -635,13 +915,12 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     s.nnz[t] = snaps[t].nnz;
   }
 
-  pipad_frame *f = new pipad_frame;
+  pipad_frame *f = new (std::nothrow) pipad_frame;
+  if (!f) return PIPAD_ERR_ALLOC;
   f->n = n;
   f->k = k;
   f->own_memory = alloc == nullptr;
-  f->short_max = (int32_t)std::max<int64_t>(0, options().short_max);
-  f->hub_threshold = (int32_t)std::max<int64_t>(f->short_max, options().hub_threshold);
-  f->hub_segment = (int32_t)std::max<int64_t>(1, options().hub_segment);
+  frame_take_options(f);
   Allocator A{alloc, alloc_ctx, f};
   f->alloc = alloc;
   f->alloc_ctx = alloc_ctx;
@@ -684,6 +963,7 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   keep1.want(&f->rowptr_c, (size_t)n + 1);
   for (int t = 0; t < k; ++t) keep1.want(&f->rowptr_d[t], (size_t)n + 1);
   keep1.want(&f->dinv, (size_t)k * n);
+  keep1.want(&f->dinv_nk, (size_t)k * n);
   {
     void *base = A.get(keep1.total);
     if (!base) return fail(PIPAD_ERR_ALLOC);
@@ -700,8 +980,7 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   }
   for (int t = 0; t < k; ++t) tmp.want(&p.bits[t], (size_t)nw[t]);
   uint32_t *pre = nullptr, *bsum = nullptr, *shortidx = nullptr, *hubidx = nullptr,
-           *segoff = nullptr, *totals = nullptr;
-  float *dinv_nk = nullptr;
+           *segoff = nullptr, *totals = nullptr, *split_total = nullptr;
   int *dflags = nullptr;
   tmp.want(&pre, (size_t)m);
   tmp.want(&bsum, std::max(((size_t)m + kScanTile - 1) / kScanTile,
@@ -709,10 +988,10 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   tmp.want(&shortidx, (size_t)scan_len_rows);
   tmp.want(&hubidx, (size_t)scan_len_rows);
   tmp.want(&segoff, (size_t)scan_len_rows);
-  tmp.want(&dinv_nk, (size_t)k * n);
   int32_t *wave_row = nullptr;
   tmp.want(&wave_row, (size_t)nw[0] + 2);
-  tmp.want(&totals, (size_t)PIPAD_MAX_K + 8);
+  tmp.want(&totals, (size_t)2 * PIPAD_MAX_K + 8);
+  tmp.want(&split_total, (size_t)PIPAD_MAX_K + 1);
   tmp.want(&dflags, (size_t)64);
   if (alloc) {
     temp = alloc(tmp.total, alloc_ctx);
@@ -770,10 +1049,13 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   }
   hipLaunchKernelGGL(k_rowptr, grid1((int64_t)n + 1, kBlock, k + 1), dim3(kBlock), 0, st, s, p,
                      pre, n);
-  hipLaunchKernelGGL(k_rowmeta, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, s, p, n, k,
-                     f->dinv, dinv_nk, shortidx, hubidx, segoff, f->short_max, f->hub_threshold,
-                     f->hub_segment);
+  if (n > 0)
+    hipLaunchKernelGGL(k_dinv, grid1(n, kBlock), dim3(kBlock), 0, st, s, n, k, f->dinv, f->dinv_nk);
   PIPAD_TRY(hipGetLastError());
+  {
+    const int rc = launch_classify(f, shortidx, hubidx, segoff, split_total, st);
+    if (rc != 0) return fail(rc);
+  }
   {
     uint32_t *three[3] = {shortidx, hubidx, segoff};
     const int rc = exclusive_scan(three, 3, scan_len_rows, bsum, st);
@@ -781,20 +1063,21 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   }
 
   // ---- the one host synchronisation: sizes of the data-dependent outputs
-  uint32_t host_totals[PIPAD_MAX_K + 8];
+  uint32_t host_totals[2 * PIPAD_MAX_K + 8];
   hipLaunchKernelGGL(k_totals, dim3(1), dim3(kWave), 0, st, p, pre, k, n, hubidx, segoff, shortidx,
-                     totals);
+                     split_total, totals);
   PIPAD_TRY(hipGetLastError());
-  PIPAD_TRY(hipMemcpyAsync(host_totals, totals, sizeof(uint32_t) * (size_t)(k + 5),
+  PIPAD_TRY(hipMemcpyAsync(host_totals, totals, sizeof(uint32_t) * (size_t)(2 * k + 6),
                            hipMemcpyDeviceToHost, st));
   PIPAD_TRY(hipStreamSynchronize(st));
 
   f->nnz_c = (int32_t)(host_totals[1] - host_totals[0]);
   for (int t = 0; t < k; ++t) f->nnz_d[t] = (int32_t)(host_totals[2 + t] - host_totals[1 + t]);
-  f->n_hub = (int32_t)host_totals[k + 2];
-  f->n_items = (int32_t)host_totals[k + 3];
-  f->n_short = (int32_t)host_totals[k + 4];
-  f->n_long = n - f->n_short - f->n_hub;
+  {
+    const int rc = set_list_sizes(f, host_totals[k + 2], host_totals[k + 3], host_totals[k + 4],
+                                  host_totals + k + 5);
+    if (rc != 0) return fail(rc);
+  }
 
   Arena keep2;
   keep2.want(&f->col_c, (size_t)f->nnz_c);
@@ -803,12 +1086,8 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     keep2.want(&f->wc[t], (size_t)f->nnz_c);
     keep2.want(&f->wd[t], (size_t)f->nnz_d[t]);
   }
-  keep2.want(&f->rows_short, (size_t)f->n_short);
-  keep2.want(&f->rows_long, (size_t)f->n_long);
-  keep2.want(&f->hub_rows, (size_t)f->n_hub);
-  keep2.want(&f->hub_item_off, (size_t)f->n_hub + 1);
-  keep2.want(&f->item_row, (size_t)f->n_items);
-  keep2.want(&f->item_seg, (size_t)f->n_items);
+  uint32_t *ulen = nullptr, *ubsum = nullptr;
+  want_lists(keep2, f, &ulen, &ubsum);
   {
     void *base = A.get(keep2.total);
     if (!base) return fail(PIPAD_ERR_ALLOC);
@@ -824,7 +1103,7 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   if (s.nnz[0] > 0) {
     auto scatter = k == 4 ? k_scatter_common<1> : k == 8 ? k_scatter_common<2>
                  : k == 16 ? k_scatter_common<4> : k_scatter_common<0>;
-    hipLaunchKernelGGL(scatter, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, pre, dinv_nk, k);
+    hipLaunchKernelGGL(scatter, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, pre, f->dinv_nk, k);
   }
   {
     int64_t all = 0, excl = 0;
@@ -842,10 +1121,12 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
                          f->dinv, n);
     }
   }
-  hipLaunchKernelGGL(k_row_lists, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, n, shortidx,
-                     hubidx, segoff, f->rows_short, f->rows_long, f->hub_rows, f->hub_item_off,
-                     f->item_row, f->item_seg);
+  launch_row_lists(n, shortidx, hubidx, segoff, f, st);
   PIPAD_TRY(hipGetLastError());
+  {
+    const int rc = build_split_arrays(f, ulen, ubsum, st);
+    if (rc != 0) return fail(rc);
+  }
   if (!alloc) {
     PIPAD_TRY(hipStreamSynchronize(st));  // the temporaries are freed next
     (void)hipFree(temp);

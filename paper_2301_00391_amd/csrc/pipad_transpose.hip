@@ -47,41 +47,16 @@ __global__ __launch_bounds__(kBlock) void k_entry_scales(const int32_t *col, int
   if (e < nnz) w[e] = dinv_t[col[e]];
 }
 
-// Row classes from the lengths of the frame's own parts (as k_rowmeta, without D^-1/2).
-struct PartRows {
-  const int32_t *rowptr_out[PIPAD_MAX_K + 1];  // common, then the k exclusive parts
-};
-
-__global__ __launch_bounds__(kBlock) void k_classify(PartRows p, int32_t n, int32_t k,
-                                                      uint32_t *shortflag, uint32_t *hubflag,
-                                                      uint32_t *nseg, int32_t short_max,
-                                                      int32_t threshold, int32_t segment) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i > n) return;
-  if (i == n) {
-    shortflag[n] = 0;
-    hubflag[n] = 0;
-    nseg[n] = 0;
-    return;
-  }
-  const int32_t lc = p.rowptr_out[0][i + 1] - p.rowptr_out[0][i];
-  int32_t ldmax = 0;
-  for (int t = 0; t < k; ++t)
-    ldmax = max(ldmax, p.rowptr_out[1 + t][i + 1] - p.rowptr_out[1 + t][i]);
-  const int64_t total = (int64_t)lc + ldmax;
-  const bool hub = total > threshold;
-  shortflag[i] = total <= short_max ? 1u : 0u;
-  hubflag[i] = hub ? 1u : 0u;
-  nseg[i] = hub ? (uint32_t)((total + segment - 1) / segment) : 0u;
-}
-
-__global__ void k_class_totals(int32_t n, const uint32_t *hubidx, const uint32_t *segoff,
-                               const uint32_t *shortidx, uint32_t *out) {
-  if (threadIdx.x == 0) {
+__global__ void k_class_totals(int32_t n, int32_t k, const uint32_t *hubidx, const uint32_t *segoff,
+                               const uint32_t *shortidx, const uint32_t *split_total,
+                               uint32_t *out) {
+  const int q = threadIdx.x;
+  if (q == 0) {
     out[0] = hubidx[n];
     out[1] = segoff[n];
     out[2] = shortidx[n];
   }
+  if (q <= k) out[3 + q] = split_total[q];
 }
 
 }  // namespace
@@ -95,16 +70,21 @@ __global__ void k_class_totals(int32_t n, const uint32_t *hubidx, const uint32_t
 int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx, hipStream_t st,
                     pipad_frame **out) {
   const int32_t n = f->n, k = f->k;
-  pipad_frame *g = new pipad_frame;
+  pipad_frame *g = new (std::nothrow) pipad_frame;
+  if (!g) return PIPAD_ERR_ALLOC;
   g->n = n;
   g->k = k;
   g->device = f->device;
   g->own_memory = alloc == nullptr;
   g->alloc = alloc;
   g->alloc_ctx = alloc_ctx;
+  g->opt = f->opt;  // the transposed frame keeps the options of the frame it comes from
   g->short_max = f->short_max;
+  g->mid_max = f->mid_max;
   g->hub_threshold = f->hub_threshold;
   g->hub_segment = f->hub_segment;
+  g->sub_log2 = f->sub_log2;
+  g->nclass = f->nclass;
   g->nnz_c = f->nnz_c;
   for (int t = 0; t < k; ++t) g->nnz_d[t] = f->nnz_d[t];
   Allocator A{alloc, alloc_ctx, g};
@@ -125,6 +105,7 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
   keep.want(&g->rowptr_c, (size_t)n + 1);
   for (int t = 0; t < k; ++t) keep.want(&g->rowptr_d[t], (size_t)n + 1);
   keep.want(&g->dinv, (size_t)k * n);
+  keep.want(&g->dinv_nk, (size_t)k * n);
   keep.want(&g->col_c, (size_t)g->nnz_c);
   for (int t = 0; t < k; ++t) {
     keep.want(&g->col_d[t], (size_t)g->nnz_d[t]);
@@ -154,7 +135,7 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
   Arena tmp;
   int32_t *rows = nullptr;
   uint32_t *sorted = nullptr, *bsum = nullptr, *shortidx = nullptr, *hubidx = nullptr,
-           *segoff = nullptr, *totals = nullptr;
+           *segoff = nullptr, *totals = nullptr, *split_total = nullptr;
   char *sort_tmp = nullptr;
   tmp.want(&rows, (size_t)max_nnz);
   tmp.want(&sorted, (size_t)max_nnz);
@@ -163,7 +144,8 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
   tmp.want(&shortidx, (size_t)scan_len);
   tmp.want(&hubidx, (size_t)scan_len);
   tmp.want(&segoff, (size_t)scan_len);
-  tmp.want(&totals, (size_t)8);
+  tmp.want(&totals, (size_t)PIPAD_MAX_K + 8);
+  tmp.want(&split_total, (size_t)PIPAD_MAX_K + 1);
   if (alloc) {
     temp = alloc(tmp.total, alloc_ctx);
   } else if (hipMalloc(&temp, tmp.total) != hipSuccess) {
@@ -174,6 +156,8 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
   tmp.assign(temp);
 
   PIPAD_TRY_T(hipMemcpyAsync(g->dinv, f->dinv, sizeof(float) * (size_t)k * n,
+                             hipMemcpyDeviceToDevice, st));
+  PIPAD_TRY_T(hipMemcpyAsync(g->dinv_nk, f->dinv_nk, sizeof(float) * (size_t)k * n,
                              hipMemcpyDeviceToDevice, st));
   for (int part = 0; part <= k; ++part) {
     const int32_t nnz = part == 0 ? f->nnz_c : f->nnz_d[part - 1];
@@ -199,35 +183,30 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
     PIPAD_TRY_T(hipGetLastError());
   }
 
-  PartRows p;
-  std::memset(&p, 0, sizeof(p));
-  p.rowptr_out[0] = g->rowptr_c;
-  for (int t = 0; t < k; ++t) p.rowptr_out[1 + t] = g->rowptr_d[t];
-  hipLaunchKernelGGL(k_classify, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, p, n, k, shortidx,
-                     hubidx, segoff, g->short_max, g->hub_threshold, g->hub_segment);
-  PIPAD_TRY_T(hipGetLastError());
+  {
+    const int rc = launch_classify(g, shortidx, hubidx, segoff, split_total, st);
+    if (rc != 0) return fail(rc);
+  }
   {
     uint32_t *three[3] = {shortidx, hubidx, segoff};
     const int rc = scan_exclusive(three, 3, scan_len, bsum, st);
     if (rc != 0) return fail(rc);
   }
-  uint32_t host_totals[3] = {0, 0, 0};
-  hipLaunchKernelGGL(k_class_totals, dim3(1), dim3(kWave), 0, st, n, hubidx, segoff, shortidx, totals);
+  uint32_t host_totals[PIPAD_MAX_K + 8] = {};
+  hipLaunchKernelGGL(k_class_totals, dim3(1), dim3(kWave), 0, st, n, k, hubidx, segoff, shortidx,
+                     split_total, totals);
   PIPAD_TRY_T(hipGetLastError());
-  PIPAD_TRY_T(hipMemcpyAsync(host_totals, totals, sizeof(host_totals), hipMemcpyDeviceToHost, st));
+  PIPAD_TRY_T(hipMemcpyAsync(host_totals, totals, sizeof(uint32_t) * (size_t)(k + 4),
+                             hipMemcpyDeviceToHost, st));
   PIPAD_TRY_T(hipStreamSynchronize(st));
-  g->n_hub = (int32_t)host_totals[0];
-  g->n_items = (int32_t)host_totals[1];
-  g->n_short = (int32_t)host_totals[2];
-  g->n_long = n - g->n_short - g->n_hub;
+  {
+    const int rc = set_list_sizes(g, host_totals[0], host_totals[1], host_totals[2], host_totals + 3);
+    if (rc != 0) return fail(rc);
+  }
 
   Arena lists;
-  lists.want(&g->rows_short, (size_t)g->n_short);
-  lists.want(&g->rows_long, (size_t)g->n_long);
-  lists.want(&g->hub_rows, (size_t)g->n_hub);
-  lists.want(&g->hub_item_off, (size_t)g->n_hub + 1);
-  lists.want(&g->item_row, (size_t)g->n_items);
-  lists.want(&g->item_seg, (size_t)g->n_items);
+  uint32_t *ulen = nullptr, *ubsum = nullptr;
+  want_lists(lists, g, &ulen, &ubsum);
   {
     void *base = A.get(lists.total);
     if (!base) return fail(PIPAD_ERR_ALLOC);
@@ -235,6 +214,10 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
   }
   launch_row_lists(n, shortidx, hubidx, segoff, g, st);
   PIPAD_TRY_T(hipGetLastError());
+  {
+    const int rc = build_split_arrays(g, ulen, ubsum, st);
+    if (rc != 0) return fail(rc);
+  }
   if (!alloc) {
     PIPAD_TRY_T(hipStreamSynchronize(st));  // the temporaries are freed next
     (void)hipFree(temp);

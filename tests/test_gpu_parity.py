@@ -12,8 +12,8 @@ from _util import check_overlap, check_y, csr_to_coo, to_gpu_snapshots
 
 pytestmark = pytest.mark.gpu
 
-DEFAULT_OPTIONS = {"short_max": 32, "hub_threshold": 2048, "hub_segment": 1024, "agg_nt": 0,
-                   "agg_parts": 7, "agg_generic": 0, "agg_coalescent": 1, "slice_cols": 0, "agg_order": 2}
+DEFAULT_OPTIONS = {"short_max": 64, "mid_max": 512, "hub_threshold": 2048, "hub_segment": 2048,
+                   "sub_classes": 1, "agg_nt": 0, "agg_generic": 0, "agg_coalescent": 1, "slice_cols": 0}
 
 torch = pytest.importorskip("torch")
 
@@ -89,12 +89,12 @@ def churned(rng, n, k, p, keep, symmetric=True):
     return out
 
 
-@pytest.mark.parametrize("nt,coalescent,order", [(0, 1, 0), (3, 2, 1)])
+@pytest.mark.parametrize("nt,coalescent,mid_max", [(0, 1, 256), (3, 2, 40)])
 @pytest.mark.parametrize("layout", ["list", "wide"])
-def test_tiny_config(pipad, nt, coalescent, order, layout):
+def test_tiny_config(pipad, nt, coalescent, mid_max, layout):
     pipad.set_option("agg_nt", nt)
     pipad.set_option("agg_coalescent", coalescent)
-    pipad.set_option("agg_order", order)
+    pipad.set_option("mid_max", mid_max)
     cfg = synth.CONFIGS["tiny"]
     s = synth.make(cfg)
     lists = [(s.rowptr[t], s.col[t]) for t in range(cfg.k)]
@@ -111,31 +111,34 @@ def test_small_config_sliding_frames(pipad, first):
 
 @pytest.mark.parametrize("k,F", [(1, 1), (2, 2), (3, 6), (4, 16), (5, 20), (8, 64), (8, 128),
                                  (2, 130), (16, 32), (3, 260), (32, 4), (8, 256), (7, 12)])
-@pytest.mark.parametrize("short_max,generic,order", [(32, 0, 0), (4, 0, 1), (4, 1, 1), (32, 0, 1)])
-def test_shapes_and_feature_widths(pipad, k, F, short_max, generic, order):
+@pytest.mark.parametrize("short_max,generic,mid_max", [(32, 0, 256), (4, 0, 12), (4, 1, 12), (2, 0, 2)])
+def test_shapes_and_feature_widths(pipad, k, F, short_max, generic, mid_max):
     pipad.set_option("short_max", short_max)
     pipad.set_option("agg_generic", generic)
-    pipad.set_option("agg_order", order)
+    pipad.set_option("mid_max", mid_max)
     rng = np.random.default_rng(1000 * k + F)
     n = 333  # several workgroups and a ragged tail
     lists = churned(rng, n, k, 0.03, 0.8)
     run_case(pipad, n, lists, F, seed=k * 7 + F, layout="wide" if F % 2 == 0 else "list")
 
 
-@pytest.mark.parametrize("short_max,threshold,segment", [(2, 6, 4), (0, 0, 1), (5, 5, 3), (0, 9, 70)])
-def test_row_classes_short_long_hub(pipad, short_max, threshold, segment):
-    """Low thresholds push rows through all three paths; hub rows are cut into segments whose
-    partial sums are added in a fixed order."""
+@pytest.mark.parametrize("sub_classes", [1, 2, 4])
+@pytest.mark.parametrize("short_max,mid_max,threshold,segment",
+                         [(2, 8, 14, 4), (0, 0, 1, 1), (5, 5, 5, 3), (0, 20, 9, 70), (3, 1000, 6, 4)])
+def test_row_classes_short_mid_hub(pipad, short_max, mid_max, threshold, segment, sub_classes):
+    """Low thresholds push rows through all three paths (whole short rows, class parts of mid rows
+    walked by lane teams, class parts of hub units walked by waves); very long rows are cut into
+    units; the partial sums of a row are added in a fixed order."""
     pipad.set_option("short_max", short_max)
+    pipad.set_option("mid_max", mid_max)
     pipad.set_option("hub_threshold", threshold)
     pipad.set_option("hub_segment", segment)
+    pipad.set_option("sub_classes", sub_classes)
     rng = np.random.default_rng(77)
     n = 500
     lists = churned(rng, n, 4, 0.04, 0.7)
-    pipad.set_option("agg_order", 1)
     run_case(pipad, n, lists, 130, seed=4)
     run_case(pipad, n, lists, 64, seed=4, layout="wide")
-    pipad.set_option("agg_order", 0)
     run_case(pipad, n, lists, 16, seed=5)
     run_case(pipad, n, lists, 9, seed=6)
     run_case(pipad, n, lists, 64, seed=7, layout="wide")
@@ -218,6 +221,7 @@ def test_library_allocator_and_determinism(pipad):
     lists = churned(rng, n, 4, 0.03, 0.8)
     run_case(pipad, n, lists, 32, seed=9, allocator="library")
     pipad.set_option("short_max", 3)
+    pipad.set_option("mid_max", 6)
     pipad.set_option("hub_threshold", 8)
     pipad.set_option("hub_segment", 8)
     snaps = [(torch.from_numpy(rp).cuda(), torch.from_numpy(c).cuda()) for rp, c in lists]
@@ -234,6 +238,7 @@ def test_aggregate_replayed_from_a_hip_graph(pipad):
     scratch), so a training loop can capture it once and replay it.  Every replay, with eager work
     and synchronisations in between, must reproduce the eager result bit for bit."""
     pipad.set_option("short_max", 2)
+    pipad.set_option("mid_max", 5)
     pipad.set_option("hub_threshold", 6)
     pipad.set_option("hub_segment", 4)
     rng = np.random.default_rng(99)
@@ -324,7 +329,8 @@ def test_allocator_failure_is_reported_not_fatal(pipad):
     n, k = 300, 3
     lists = churned(rng, n, k, 0.05, 0.8)
     pipad.set_option("short_max", 2)
-    pipad.set_option("hub_threshold", 6)   # hub rows exist, so aggregate needs scratch
+    pipad.set_option("mid_max", 4)
+    pipad.set_option("hub_threshold", 6)   # split rows exist, so aggregate needs scratch
     pipad.set_option("hub_segment", 4)
     snaps = [(torch.from_numpy(rp).cuda(), torch.from_numpy(c).cuda()) for rp, c in lists]
     arr = (binding._Csr * k)()
@@ -470,9 +476,9 @@ def test_update_fused_into_the_aggregation(pipad, k, F, Fo, with_bias, with_a):
     run_update_case(pipad, n, lists, F, Fo, seed=k + F, with_bias=with_bias, with_a=with_a)
 
 
-def test_update_fused_with_long_and_hub_rows_and_padded_input_rows(pipad):
-    pipad.set_option("agg_order", 1)
+def test_update_fused_with_mid_and_hub_rows_and_padded_input_rows(pipad):
     pipad.set_option("short_max", 3)
+    pipad.set_option("mid_max", 7)
     pipad.set_option("hub_threshold", 9)
     pipad.set_option("hub_segment", 4)
     rng = np.random.default_rng(4)
@@ -545,11 +551,13 @@ def transpose_csr(n, rowptr, col):
 
 @pytest.mark.parametrize("k,n,p,keep,F,classes", [(3, 300, 0.05, 0.7, 24, None), (1, 64, 0.2, 1.0, 4, None),
                                                   (8, 1500, 0.01, 0.9, 64, None),
-                                                  (4, 400, 0.05, 0.7, 16, (2, 8, 4))])
+                                                  (4, 400, 0.05, 0.7, 16, (2, 8, 4)),
+                                                  (4, 400, 0.05, 0.7, 16, (2, 2, 4))])
 def test_transposed_frame_of_directed_patterns(pipad, k, n, p, keep, F, classes):
     if classes:
         pipad.set_option("short_max", classes[0])
-        pipad.set_option("hub_threshold", classes[1])
+        pipad.set_option("mid_max", classes[1])
+        pipad.set_option("hub_threshold", 12)
         pipad.set_option("hub_segment", classes[2])
     rng = np.random.default_rng(1000 + k + n)
     lists = churned(rng, n, k, p, keep, symmetric=False)
@@ -624,8 +632,9 @@ def test_randomised_frames(pipad, seed):
         rowptr = np.concatenate([[0], np.cumsum(M.sum(axis=1))]).astype(np.int32)
         lists.append((rowptr, np.nonzero(M)[1].astype(np.int32)))
     pipad.set_option("short_max", int(rng.choice([0, 4, 32])))
-    pipad.set_option("hub_threshold", int(rng.choice([8, 100, 2048])))
-    pipad.set_option("hub_segment", int(rng.choice([3, 64, 1024])))
-    pipad.set_option("agg_order", int(rng.integers(3)))
+    pipad.set_option("mid_max", int(rng.choice([0, 16, 256])))
+    pipad.set_option("hub_threshold", int(rng.choice([8, 100, 8192])))
+    pipad.set_option("hub_segment", int(rng.choice([3, 64, 8192])))
+    pipad.set_option("sub_classes", int(rng.choice([1, 2, 4])))
     F = int(rng.choice([1, 4, 7, 16, 64, 96]))
     run_case(pipad, n, lists, F, seed=seed, layout="list" if seed % 2 else "wide")

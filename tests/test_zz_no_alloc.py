@@ -71,16 +71,18 @@ def both_entry_points(lib, frame, X, n, k, F):
 def test_static_scratch_entry_point_matches_the_allocating_one(pipad):
     from paper_2301_00391_amd import binding
     lib = pipad.load_library()
-    saved = {key: pipad.get_option(key) for key in ("short_max", "hub_threshold", "hub_segment")}
+    saved = {key: pipad.get_option(key) for key in ("short_max", "mid_max", "hub_threshold", "hub_segment")}
     try:
-        # low thresholds: many rows are cut into segments, so the scratch array is really used
-        pipad.set_option("short_max", 2)
-        pipad.set_option("hub_threshold", 6)
-        pipad.set_option("hub_segment", 4)
+        # low thresholds: most rows are split (mid rows, hub rows, hub rows cut into units), so
+        # the scratch array is really used
+        pipad.set_option("short_max", 8)
+        pipad.set_option("mid_max", 20)
+        pipad.set_option("hub_threshold", 24)
+        pipad.set_option("hub_segment", 16)
         rng = np.random.default_rng(2024)
         # two calls in a row on the same GPU: the second, smaller one finds the first one's partial
         # sums still in the array
-        for n, k, F, p in ((900, 4, 48, 0.03), (310, 3, 16, 0.05)):
+        for n, k, F, p in ((900, 4, 32, 0.03), (310, 3, 16, 0.05)):
             lists = churned(rng, n, k, p, 0.8)
             frame, _snaps = build_frame_abi(lib, binding, lists, n)
             Xh = [synth.features(11, t, n, F) for t in range(k)]
@@ -100,15 +102,16 @@ def test_static_scratch_entry_point_matches_the_allocating_one(pipad):
 def test_static_scratch_entry_point_rejects_what_does_not_fit(pipad):
     from paper_2301_00391_amd import binding
     lib = pipad.load_library()
-    saved = {key: pipad.get_option(key) for key in ("short_max", "hub_threshold", "hub_segment")}
+    saved = {key: pipad.get_option(key) for key in ("short_max", "mid_max", "hub_threshold", "hub_segment")}
     try:
-        # every entry its own segment: about 25 k segments x k*F = 1024 floats > 64 MiB
+        # every entry a unit of its own: about 10 k units x 8 classes x k*F = 1024 floats > 64 MiB
         pipad.set_option("short_max", 0)
-        pipad.set_option("hub_threshold", 0)
+        pipad.set_option("mid_max", 0)
+        pipad.set_option("hub_threshold", 1)
         pipad.set_option("hub_segment", 1)
         rng = np.random.default_rng(5)
         n, k, F = 1000, 8, 128
-        lists = churned(rng, n, k, 0.025, 1.0)
+        lists = churned(rng, n, k, 0.005, 1.0)
         frame, _snaps = build_frame_abi(lib, binding, lists, n)
         X = [torch.zeros((n, F), device="cuda:0") for _ in range(k)]
         Y = [torch.full((n, F), 3.0, device="cuda:0") for _ in range(k)]
