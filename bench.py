@@ -35,26 +35,128 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E peak
 
 
+def kernel_sources_sha() -> str:
+    """Fingerprint of the HIP sources and headers the library is built from."""
+    import hashlib
+    h = hashlib.sha256()
+    for d in (os.path.join(ROOT, "paper_2301_00391_amd", "csrc"), os.path.join(ROOT, "include")):
+        for name in sorted(os.listdir(d)):
+            if name.endswith((".hip", ".h")):
+                h.update(name.encode())
+                h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def traffic_profile_path(workload: str) -> str:
+    return os.path.join(ROOT, "profiles", f"k_aggregate_{workload}_l2_miss_traffic.txt")
+
+
 def measured_traffic(workload: str):
-    """HBM bytes per aggregate call from the committed rocprofv3 counter summary of this workload
-    (FETCH_SIZE / WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a
-    plain copy kernel of known size); None when no summary is there."""
-    path = os.path.join(ROOT, "profiles", f"k_aggregate_{workload}_hbm_traffic.txt")
+    """Bytes one aggregate call moves between the L2s and the memory side (fabric traffic: HBM or
+    the memory-side cache), from the committed rocprofv3 counter summary of this workload:
+    FETCH_SIZE / WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a
+    plain copy kernel of known size.  Returns (bytes or None, fingerprint of the kernel sources the
+    summary was taken with or None): the bytes are only reported when the summary was taken with
+    the kernel sources of this tree."""
+    path = traffic_profile_path(workload)
     if not os.path.exists(path):
-        return None
-    vals = {}
+        return None, None
+    vals, sha = {}, None
     for line in open(path):
-        if ":" in line and not line.startswith("#"):
+        if line.startswith("kernel_sources_sha:"):
+            sha = line.split(":", 1)[1].strip()
+        elif ":" in line and not line.startswith("#"):
             key, _, val = line.partition(":")
             try:
                 vals[key.strip()] = float(val.split()[0])
             except (ValueError, IndexError):
                 pass
+    if sha != kernel_sources_sha():
+        return None, sha
     try:
         return int((vals["fetch_size_kib"] * vals["fetch_scale"] +
-                    vals["write_size_kib"] * vals["write_scale"]) * 1024)
+                    vals["write_size_kib"] * vals["write_scale"]) * 1024), sha
     except KeyError:
-        return None
+        return None, sha
+
+
+def write_traffic_profile(workload: str, dirs, bench_line: dict) -> None:
+    """--profile-summary: turns the rocprofv3 CSV output of four runs of this script (kernel trace,
+    FETCH_SIZE, WRITE_SIZE, L2 hits/misses; see the command lines it writes into the files) into
+    the two short summaries kept under profiles/ for this workload."""
+    import csv
+    import glob
+    import re
+
+    def find(d, name):
+        hits = glob.glob(os.path.join(d, "**", name), recursive=True)
+        if not hits:
+            raise SystemExit(f"no {name} under {d}")
+        return hits[0]
+
+    def kname(n):
+        m = re.search(r"(k_[a-z_]+)", n)
+        return m.group(1) if m else n[:40]
+
+    kt, pf, pw, pl = dirs
+    args = f"--workload {workload} --steps {bench_line['steps']} --warmup {bench_line['warmup']} --no-cpu"
+    head = (f"# bench.py, workload {workload} (N={bench_line['config']['n']}, k={bench_line['config']['k']}, "
+            f"F={bench_line['config']['F']}), one MI355X, kernel sources {kernel_sources_sha()}\n")
+    rows = list(csv.DictReader(open(find(kt, "bench_kernel_stats.csv"))))
+    out = [head.rstrip(),
+           f"# command: cd /tmp && export TMPDIR=/tmp && rocprofv3 --kernel-trace --stats -d <out> -o bench "
+           f"--output-format csv -- python3 bench.py {args}",
+           f"# bench.py in the same run: ms_per_step {bench_line['ms_per_step']:.3f}, aggregate_ms (HIP events) "
+           f"{bench_line['aggregate_ms']:.3f}, build_overlap_ms {bench_line['build_overlap_ms']:.3f}", "",
+           f"{'kernel':28s} {'calls':>6s} {'avg_us':>10s} {'min_us':>10s} {'max_us':>10s} {'total_ms':>10s} {'pct':>6s}"]
+    agg_us = 0.0
+    for r in rows:
+        n = kname(r["Name"])
+        if not n.startswith("k_"):
+            continue
+        out.append(f"{n:28s} {r['Calls']:>6s} {float(r['AverageNs'])/1e3:10.1f} {float(r['MinNs'])/1e3:10.1f} "
+                   f"{float(r['MaxNs'])/1e3:10.1f} {float(r['TotalDurationNs'])/1e6:10.2f} {float(r['Percentage']):6.2f}")
+        if n in ("k_aggregate", "k_split_finish"):
+            agg_us += float(r["AverageNs"]) / 1e3
+    out += ["", f"k_aggregate + k_split_finish average per call: {agg_us/1e3:.3f} ms  (HIP-event bracket of "
+                f"pipad_frame_aggregate in the same run: {bench_line['aggregate_ms']:.3f} ms)"]
+    open(os.path.join(ROOT, "profiles", f"bench_{workload}_kernel_trace.txt"), "w").write("\n".join(out) + "\n")
+
+    def mean_counter(d, counter):
+        tot = {}
+        for r in csv.DictReader(open(find(d, "bench_counter_collection.csv"))):
+            n = kname(r["Kernel_Name"])
+            if r["Counter_Name"] == counter and n in ("k_aggregate", "k_split_finish"):
+                tot.setdefault(n, []).append(float(r["Counter_Value"]))
+        return sum(sum(v) / len(v) for v in tot.values()), max((len(v) for v in tot.values()), default=0)
+
+    f, nf = mean_counter(pf, "FETCH_SIZE")
+    w, _ = mean_counter(pw, "WRITE_SIZE")
+    hit, _ = mean_counter(pl, "TCC_HIT_sum")
+    miss, _ = mean_counter(pl, "TCC_MISS_sum")
+    tb = f * 2 * 1024 + w * 1024
+    algo = bench_line["roofline"]["algorithmic_bytes"]
+    t = [head.rstrip(),
+         "# Traffic between the L2s and the memory side (the fabric: served by HBM or by the 256 MB memory-side",
+         "# cache) of one pipad_frame_aggregate call = k_aggregate + k_split_finish; rocprofv3 counters, KiB per dispatch.",
+         f"# commands (one run per line): cd /tmp && export TMPDIR=/tmp && rocprofv3 --pmc FETCH_SIZE -d <out> -o bench "
+         f"--output-format csv -- python3 bench.py {args}",
+         "#                              ... --pmc WRITE_SIZE ...  |  ... --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum ...",
+         "# summary written by: python3 bench.py --profile-summary <kernel-trace dir> <FETCH dir> <WRITE dir> <L2 dir> "
+         f"--workload {workload}",
+         "# calibration (same counters on a plain float4 copy kernel, 2 GiB -> 2 GiB): FETCH_SIZE read 1048587 KiB for",
+         "#   2097152 KiB actually read (it counts each 128-byte read request as 64 bytes) -> scale 2.0; WRITE_SIZE read",
+         "#   2097152 KiB for 2097152 KiB written -> scale 1.0",
+         f"# mean over {nf} dispatches:",
+         f"kernel_sources_sha: {kernel_sources_sha()}",
+         f"fetch_size_kib: {f:.0f}", f"write_size_kib: {w:.0f}", "fetch_scale: 2.0", "write_scale: 1.0",
+         f"l2_hits_per_call: {hit:.4g}", f"l2_misses_per_call: {miss:.4g}",
+         f"l2_hit_rate: {hit / max(hit + miss, 1):.3f}",
+         f"# => {tb/1e9:.2f} GB per call between L2 and memory side; algorithmic (minimal) bytes of the call "
+         f"{algo/1e9:.2f} GB; ratio {tb/algo:.2f}",
+         f"# => at aggregate_ms {bench_line['aggregate_ms']:.3f}: {tb/bench_line['aggregate_ms']/1e6:.0f} GB/s of fabric traffic"]
+    open(traffic_profile_path(workload), "w").write("\n".join(t) + "\n")
+    print("\n".join(out) + "\n\n" + "\n".join(t))
 
 
 def log(*a):
@@ -143,13 +245,24 @@ def main() -> int:
                     help="time pipad_frame_aggregate_update (the GCN layer with FO output columns: "
                          "aggregation + fully connected update) instead of the aggregation alone")
     ap.add_argument("--cold", action="store_true", help="flush the caches between steps")
+    ap.add_argument("--profile-summary", nargs=4, metavar="DIR",
+                    help="no GPU needed: write profiles/bench_<workload>_kernel_trace.txt and "
+                         "profiles/k_aggregate_<workload>_l2_miss_traffic.txt from four rocprofv3 output "
+                         "directories (kernel trace, FETCH_SIZE, WRITE_SIZE, TCC hit/miss) of this "
+                         "script; the bench line of the kernel-trace run is read from stdin")
     ap.add_argument("--ceilings", action="store_true",
                     help="only measure the streaming and gather ceilings of this GPU (full sweep) "
                          "and print them as one JSON line")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the short measurement of the streaming and gather ceilings")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--cpu-threads", type=int, default=0, help="oracle threads (0 = all)")
     args = ap.parse_args()
+    if args.profile_summary:
+        line = json.loads(sys.stdin.read().strip().splitlines()[-1])
+        write_traffic_profile(args.workload, args.profile_summary, line)
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
               "use --gpus 1", file=sys.stderr)
@@ -296,6 +409,7 @@ def main() -> int:
     value = updates * args.epochs / (ms_per_step * 1e-3)
     nnz_c, nnz_d = nnz_c_f[0], nnz_d_f[0]
     nnz_t = nnz_s[:k]
+    traffic, traffic_sha = (None, None) if Fo else measured_traffic(args.workload)
 
     out = {
         "metric": "frame-aggregation edge*feat updates/s (build_overlap + aggregate per frame, k=%d)" % k,
@@ -325,14 +439,34 @@ def main() -> int:
         "aggregate_ms_median": float(np.median(agg_all)),
         "aggregate_updates_per_s": updates / (agg_ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if Fo else measured_traffic(args.workload),
-                     "kernel": ("pipad_frame_aggregate_update (k_aggregate_update + k_hub_finish)" if Fo
-                                else "pipad_frame_aggregate (k_aggregate + k_hub_finish)"),
-                     "algorithmic_bytes": int(bytes_min)},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_kind": "bytes between the L2s and the memory side (HBM or memory-side cache) "
+                                     "per aggregate call, from " + os.path.relpath(traffic_profile_path(args.workload), ROOT),
+                     "traffic_kernel_sources": traffic_sha, "kernel_sources": kernel_sources_sha(),
+                     "kernel": ("pipad_frame_aggregate_update (k_aggregate_update + k_split_finish)" if Fo
+                                else "pipad_frame_aggregate (k_aggregate + k_split_finish)"),
+                     "algorithmic_bytes": int(bytes_min),
+                     # the row gathers themselves: every edge.feat update pulls 4 bytes through the
+                     # vector memory path even when the caches serve them all
+                     "gather_bytes": int(4 * updates)},
         "paper_context": "PiPAD reports 1.22x-9.57x end-to-end training speedup on a V100 (no absolute "
                          "number for this path)",
     }
     del out["config"]["model"]
+    if not args.no_ceilings:
+        # what this GPU delivers, measured now with the kernels of include/pipad_ceilings.h: the
+        # attainable time of one aggregate call is bounded by its algorithmic bytes at the
+        # streaming rate AND by its gathered bytes at the rate of row gathers that all hit the L2
+        ceil = measure_ceilings(pipad, torch, full=False)
+        roof = out["roofline"]
+        roof["stream_read_GBps"] = ceil["stream_read_GBps"]
+        roof["gather_peak"] = ceil["gather_256B_L2_GBps"]
+        roof["gather_peak_kind"] = "256-byte row gathers, working set resident in one L2, GB/s"
+        roof["gather_MALL_GBps"] = ceil["gather_256B_MALL_GBps"]
+        roof["gather_HBM_GBps"] = ceil["gather_256B_HBM_GBps"]
+        roof["attainable_ms"] = max(bytes_min / ceil["stream_read_GBps"],
+                                    4 * updates / ceil["gather_256B_L2_GBps"]) / 1e6
+        roof["frac_of_attainable"] = roof["attainable_ms"] / agg_ms
 
     if not args.no_cpu:
         import oracle

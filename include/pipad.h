@@ -42,8 +42,9 @@ typedef enum pipad_status {
   PIPAD_ERR_ALLOC = -3,       /* device allocation failed (callback returned NULL / hipMalloc)  */
   PIPAD_ERR_TOO_LARGE = -4,   /* a size does not fit the int32 index space                      */
   PIPAD_ERR_HIP = -5,         /* a HIP runtime call failed; see pipad_last_hip_error()          */
-  PIPAD_ERR_SCRATCH = -6      /* pipad_frame_aggregate_static: the partial sums of this frame   *
-                               * and F do not fit the fixed scratch array; nothing was enqueued */
+  PIPAD_ERR_SCRATCH = -6      /* the partial sums of this frame and F do not fit the scratch     *
+                               * buffer and it cannot grow now (pipad_frame_aggregate_static; any *
+                               * aggregation under stream capture); nothing was enqueued         */
 } pipad_status;
 
 /* One sparse 0/1 pattern in CSR.  Used for the input snapshots and for borrowed views of a
@@ -64,7 +65,8 @@ typedef struct pipad_frame pipad_frame_t;
  * usable on `stream`'s device, or NULL on failure.  Memory obtained through the callback is owned
  * by the caller and must stay valid until pipad_frame_destroy(); the library never frees it.  The
  * callback and its ctx must stay callable until then too: besides the frame's own buffers it
- * serves the temporaries of the build and the scratch buffer of pipad_frame_aggregate. */
+ * serves the temporaries of the build (which the caller may take back early, see
+ * pipad_frame_temporaries) and the scratch buffer of pipad_frame_aggregate. */
 typedef void *(*pipad_alloc_fn)(size_t bytes, void *ctx);
 
 #define PIPAD_VALIDATE 1u /* flag: check on the device that every input snapshot is canonical */
@@ -86,7 +88,7 @@ typedef void *(*pipad_alloc_fn)(size_t bytes, void *ctx);
  *           otherwise every device buffer is obtained through alloc(bytes, ctx) and no
  *           hipMalloc / hipFree is issued
  *   stream  stream the kernels run on.  The call synchronises with it once (sizes of the outputs
- *           are data dependent and are read back).  With alloc == NULL the frame is complete on
+ *           are data dependent and are read back; PIPAD_VALIDATE adds a second synchronisation).  With alloc == NULL the frame is complete on
  *           return; with a callback the last kernels may still be running on `stream`, so the
  *           inputs must stay valid, and the frame is used, in stream order.
  *   out     receives the new frame.
@@ -94,6 +96,23 @@ typedef void *(*pipad_alloc_fn)(size_t bytes, void *ctx);
 int pipad_frame_build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags,
                               pipad_alloc_fn alloc, void *alloc_ctx, void *stream,
                               pipad_frame_t **out);
+
+/* With a caller allocator, one of the buffers a build (or pipad_frame_transpose) obtained holds
+ * only temporaries: the frame never touches it again once the work that the build enqueued on its
+ * stream has completed.  This call reports that buffer (*ptr, *bytes as requested from the
+ * callback; NULL / 0 with the library's own allocator, which frees its temporaries itself, or
+ * when it was already taken) and the frame forgets it: the caller may release it after a
+ * stream-ordered point behind the build, long before pipad_frame_destroy(). */
+int pipad_frame_temporaries(pipad_frame_t *frame, void **ptr, size_t *bytes);
+
+/* Row stride, in floats, that the feature matrices X should have when their rows are gathered
+ * by pipad_frame_aggregate: the smallest ODD number of 128-byte lines that holds F floats
+ * (F = 64 -> 96, F = 128 -> 160, F <= 32 -> 32).  The call works with any ldx >= F; but with a
+ * power-of-two stride the memory channel of a row is decided by a few bits of the node id, and
+ * when popular nodes share those bits (ids of R-MAT-like generators do) their rows crowd onto a
+ * few channels: measured on a 1M-node R-MAT frame at F = 64, ldx = 64 is 4-8 % slower than
+ * ldx = 96.  The padding is never read.  Returns a negative pipad_status for F < 1. */
+int64_t pipad_recommended_row_stride(int32_t F);
 
 /* Borrowed views (valid until the frame is destroyed) of the overlap part and of the exclusive
  * part of snapshot t; see pipad_csr_t for the guarantees. */
@@ -121,17 +140,19 @@ int pipad_frame_shape(const pipad_frame_t *frame, int32_t *n, int32_t *k);
  *   Y    host array of k device pointers, row stride ldy >= F; written exactly once per element
  *        (columns >= F of a wider row are not touched).  Y must not overlap X.
  *   The current HIP device must be the one the frame was built on (else PIPAD_ERR_INVALID_ARG).
- *   Only enqueues work on `stream`; no host synchronisation.  The first call with a larger k*F
- *   than any before may allocate (and keep) a scratch buffer for the partial sums of very long
- *   rows.  Two aggregations of the SAME frame must not run concurrently (they share that scratch).
- *   Apart from that allocation the call consists of kernel launches only, so it can be recorded
- *   into a HIP graph (stream capture) once an eager call with the same or a larger k*F has sized
- *   the scratch; with the library's own allocator, growing it while the stream is capturing fails
- *   (PIPAD_ERR_HIP or PIPAD_ERR_ALLOC) and nothing is enqueued.
+ *   The frame is only read, except for its scratch buffer (hence the non-const pointer): the
+ *   partial sums of rows that are summed in several parts go through it.  The first call of a
+ *   frame, and any call with a larger k*F than all before, allocates it (through the frame's
+ *   allocator; with the library's own allocator a buffer that is replaced is freed after a
+ *   hipDeviceSynchronize).  All other calls only enqueue kernels on `stream`, without host
+ *   synchronisation, so they can be recorded into a HIP graph (stream capture) once an eager call
+ *   with the same or a larger k*F has sized the scratch; a call that would have to allocate while
+ *   `stream` is being captured returns PIPAD_ERR_SCRATCH with nothing enqueued.
+ *   Two aggregations of the SAME frame must not run concurrently (they share that scratch).
  *   Results are deterministic: same inputs, same bits.
  */
-int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *const *X,
-                          int64_t ldx, float *const *Y, int64_t ldy, void *stream);
+int pipad_frame_aggregate(pipad_frame_t *frame, int32_t F, const float *const *X, int64_t ldx,
+                          float *const *Y, int64_t ldy, void *stream);
 
 /* pipad_frame_aggregate for callers that cannot allocate device memory: code under HIP graph
  * (stream) capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
@@ -142,7 +163,8 @@ int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *co
  * allocating routine; the array's address on a device is looked up once, at the first
  * pipad_frame_build_overlap or pipad_frame_aggregate_static on that device.
  *   Returns PIPAD_ERR_SCRATCH, with nothing enqueued, when the frame needs more than the array
- *   holds: (number of split-row segments) * k * (F rounded up to the slice width) floats.
+ *   holds: (units of rows longer than "mid_max") * (column classes) * k * (F rounded up to the
+ *   slice width) floats.
  *   All calls on one GPU share the array: calls that overlap in time on that GPU (different
  *   streams, or different frames) race on it and give wrong results; calls ordered on one stream
  *   are safe.  Nothing in the array has to be cleared between calls: every partial sum is written
@@ -173,7 +195,7 @@ int pipad_frame_aggregate_static(const pipad_frame_t *frame, int32_t F, const fl
  *          H, A, X, W must not overlap.
  *   Stream, device, scratch and determinism rules are those of pipad_frame_aggregate.
  */
-int pipad_frame_aggregate_update(const pipad_frame_t *frame, int32_t F, const float *const *X,
+int pipad_frame_aggregate_update(pipad_frame_t *frame, int32_t F, const float *const *X,
                                  int64_t ldx, const float *W, int64_t ldw, const float *bias,
                                  int32_t Fo, float *const *A, int64_t lda, float *const *H,
                                  int64_t ldh, void *stream);

@@ -15,15 +15,13 @@ def coalescent_row_bytes(snapshots: int, feat: int) -> int:
 
 
 def padded_row_stride(feat: int) -> int:
-    """Row stride, in floats, for a feature matrix whose rows are gathered: the smallest odd
-    multiple of 128 bytes that holds ``feat`` floats.  A power-of-two stride ties a row's memory
-    channel to a few bits of the node id; when popular nodes share those bits (R-MAT ids do) their
-    rows crowd onto a few channels.  An odd number of 128-byte lines per row spreads them evenly;
-    the padding is never read."""
-    lines = (feat * 4 + 127) // 128
-    if lines % 2 == 0:
-        lines += 1
-    return lines * 32
+    """pipad_recommended_row_stride: the row stride, in floats, that a feature matrix whose rows are
+    gathered should have (the smallest odd number of 128-byte lines that holds ``feat`` floats; the
+    reason is in include/pipad.h)."""
+    stride = int(load_library().pipad_recommended_row_stride(int(feat)))
+    if stride < 0:
+        raise ValueError("feat must be at least 1")
+    return stride
 
 
 __all__ = ["Frame", "PipadError", "frame_aggregate", "frame_aggregate_update", "frame_build_overlap", "frame_transpose", "get_option",

@@ -56,6 +56,8 @@ SIGNATURES = {
                                                     _vp, _i32, ctypes.POINTER(_vp), _i64,
                                                     ctypes.POINTER(_vp), _i64, _vp]),
     "pipad_frame_transpose": (ctypes.c_int, [_vp, _vp, _vp, _vp, ctypes.POINTER(_vp)]),
+    "pipad_frame_temporaries": (ctypes.c_int, [_vp, ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_size_t)]),
+    "pipad_recommended_row_stride": (ctypes.c_int64, [_i32]),
     "pipad_frame_destroy": (None, [_vp]),
     "pipad_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "pipad_last_hip_error": (ctypes.c_char_p, []),
@@ -129,16 +131,46 @@ Snapshot = Tuple[torch.Tensor, torch.Tensor]  # (rowptr int32[n+1], colidx int32
 class Frame:
     """Owner of one ``pipad_frame_t``.  Built by :func:`frame_build_overlap`."""
 
-    def __init__(self, handle: int, n: int, k: int, device, buffers: list, callback=None):
+    def __init__(self, handle: int, n: int, k: int, device, buffers: list, callback=None,
+                 stream=None):
         self._h = handle
         self.n, self.k, self.device = n, k, device
         self._buffers = buffers  # torch tensors handed to the library through the allocator
         self._callback = callback  # the library may call it again (aggregate scratch)
+        # torch's allocator hands memory out, and takes it back, in the order of the stream that
+        # was current at the allocation; work on any other stream has to be waited for in close()
+        self._alloc_stream = torch.cuda.current_stream(device)
+        self._streams = {stream if stream is not None else self._alloc_stream}
+        self._temp = None
+        if callback is not None:
+            # the build's temporaries can go back to the allocator as soon as the build's kernels
+            # have run: remember the buffer and an event behind them
+            ptr, size = _vp(), ctypes.c_size_t()
+            _check(load_library().pipad_frame_temporaries(handle, ctypes.byref(ptr), ctypes.byref(size)))
+            if ptr.value:
+                held = [b for b in buffers if b.data_ptr() == ptr.value]
+                event = torch.cuda.Event()
+                event.record(next(iter(self._streams)))
+                self._temp = (held, event)
+
+    def _release_temporaries(self, wait: bool = False) -> None:
+        if self._temp is not None and (wait or self._temp[1].query()):
+            if wait:
+                self._temp[1].synchronize()
+            held = {id(b) for b in self._temp[0]}
+            self._buffers[:] = [b for b in self._buffers if id(b) not in held]
+            self._temp = None
 
     def close(self) -> None:
         if self._h:
+            # work of this frame may still be running on streams other than the one its buffers
+            # are ordered on
+            for s in self._streams:
+                if s != self._alloc_stream:
+                    s.synchronize()
             load_library().pipad_frame_destroy(self._h)
             self._h = None
+            self._temp = None
             self._buffers = []
 
     def __del__(self):
@@ -205,7 +237,7 @@ def frame_transpose(frame: Frame, allocator: str = "torch", stream=None) -> Fram
         status = lib.pipad_frame_transpose(frame._h, ctypes.cast(cb, _vp) if cb is not None else None,
                                            None, _stream_handle(stream), ctypes.byref(out))
     _check(status)
-    return Frame(out.value, frame.n, frame.k, frame.device, buffers, cb)
+    return Frame(out.value, frame.n, frame.k, frame.device, buffers, cb, stream)
 
 
 def frame_build_overlap(snapshots: Sequence[Snapshot], validate: bool = False,
@@ -240,7 +272,7 @@ def frame_build_overlap(snapshots: Sequence[Snapshot], validate: bool = False,
             ctypes.cast(cb, _vp) if cb is not None else None, None,
             _stream_handle(stream), ctypes.byref(out))
     _check(status)
-    return Frame(out.value, n, k, device, buffers, cb)
+    return Frame(out.value, n, k, device, buffers, cb, stream)
 
 
 Features = Union[torch.Tensor, Sequence[torch.Tensor]]
@@ -294,6 +326,8 @@ def frame_aggregate(frame: Frame, X: Features, Y: Optional[Features] = None, str
         raise ValueError("X and Y must have the same number of feature columns")
     xa = (_vp * k)(*xp)
     ya = (_vp * k)(*yp)
+    frame._release_temporaries()
+    frame._streams.add(stream if stream is not None else torch.cuda.current_stream(frame.device))
     with torch.cuda.device(frame.device):
         fn = lib.pipad_frame_aggregate_static if static_scratch else lib.pipad_frame_aggregate
         _check(fn(frame._h, F, xa, ldx, ya, ldy, _stream_handle(stream)))
@@ -329,6 +363,8 @@ def frame_aggregate_update(frame: Frame, X: Features, W: torch.Tensor,
         if Fa != F:
             raise ValueError("A must have F feature columns")
         aa = (_vp * k)(*ap)
+    frame._release_temporaries()
+    frame._streams.add(stream if stream is not None else torch.cuda.current_stream(frame.device))
     with torch.cuda.device(frame.device):
         _check(lib.pipad_frame_aggregate_update(
             frame._h, F, xa, ldx, W.data_ptr(), W.stride(0) if F > 1 else max(Fo, W.stride(0)),

@@ -1096,9 +1096,9 @@ int static_scratch(float **ptr, size_t *floats) {
   return PIPAD_OK;
 }
 
-int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t ldx,
-                     float *const *Y, int64_t ldy, hipStream_t st, const UpdateSpec *upd,
-                     float *fixed_scratch, size_t fixed_scratch_floats) {
+int aggregate_launch(const pipad_frame *f, int32_t F, const float *const *X, int64_t ldx,
+                     float *const *Y, int64_t ldy, hipStream_t st, ScratchRef scratch,
+                     const UpdateSpec *upd) {
   if (f->n == 0) return PIPAD_OK;
   const Options &opt = f->opt;  // as they stood when the frame was built
   AggArgs a;
@@ -1233,9 +1233,8 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
   // scratch for the partial sums: one slice-wide vector per class part (per hub unit for the
   // coalescent kernel) and slice
   const size_t need = (coalescent ? (size_t)f->n_items : (size_t)a.nvp) * (size_t)a.nslices * (size_t)sw;
-  if (fixed_scratch) {
-    if (need > fixed_scratch_floats) return PIPAD_ERR_SCRATCH;
-  } else if (need > f->partial_floats) {
+  if (need > *scratch.floats) {
+    if (scratch.fixed) return PIPAD_ERR_SCRATCH;
     // growing means allocating: not while the stream is being captured into a graph
     hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(st, &capturing) != hipSuccess) {
@@ -1250,21 +1249,21 @@ int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t l
       if (!ptr) return PIPAD_ERR_ALLOC;
     } else {
       // the old buffer may still be in use by earlier aggregations of this frame
-      if (f->partial) {
+      if (*scratch.ptr) {
         PIPAD_HIP(hipDeviceSynchronize());
-        (void)hipFree(f->partial);
+        (void)hipFree(*scratch.ptr);
       }
-      f->partial = nullptr;
-      f->partial_floats = 0;
+      *scratch.ptr = nullptr;
+      *scratch.floats = 0;
       if (hipMalloc(&ptr, need * sizeof(float)) != hipSuccess) {
         (void)hipGetLastError();
         return PIPAD_ERR_ALLOC;
       }
     }
-    f->partial = static_cast<float *>(ptr);
-    f->partial_floats = need;
+    *scratch.ptr = static_cast<float *>(ptr);
+    *scratch.floats = need;
   }
-  a.partial = fixed_scratch ? fixed_scratch : f->partial;
+  a.partial = *scratch.ptr;
   if (coalescent)
     return cvec == 4 ? launch_coalescent<4>(a, st)
                      : cvec == 2 ? launch_coalescent<2>(a, st) : launch_coalescent<1>(a, st);

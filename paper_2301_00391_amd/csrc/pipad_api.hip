@@ -82,8 +82,8 @@ int pipad_frame_shape(const pipad_frame_t *f, int32_t *n, int32_t *k) {
   return PIPAD_OK;
 }
 
-int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *const *X,
-                          int64_t ldx, float *const *Y, int64_t ldy, void *stream) {
+int pipad_frame_aggregate(pipad_frame_t *frame, int32_t F, const float *const *X, int64_t ldx,
+                          float *const *Y, int64_t ldy, void *stream) {
   if (!frame || !X || !Y || F < 1 || ldx < F || ldy < F) return PIPAD_ERR_INVALID_ARG;
   if (frame->n > 0)
     for (int t = 0; t < frame->k; ++t)
@@ -95,9 +95,9 @@ int pipad_frame_aggregate(const pipad_frame_t *frame, int32_t F, const float *co
     if (hipGetDevice(&dev) != hipSuccess) return pipad::hip_fail(hipGetLastError(), "hipGetDevice");
     if (dev != frame->device) return PIPAD_ERR_INVALID_ARG;  // frames are tied to their GPU
   }
-  // the frame's scratch buffer is the only mutable state
-  return pipad::aggregate_launch(const_cast<pipad_frame *>(frame), F, X, ldx, Y, ldy,
-                                 static_cast<hipStream_t>(stream));
+  // the frame's scratch buffer is the only state an aggregation changes
+  return pipad::aggregate_launch(frame, F, X, ldx, Y, ldy, static_cast<hipStream_t>(stream),
+                                 pipad::ScratchRef{&frame->partial, &frame->partial_floats, false});
 }
 
 int pipad_frame_aggregate_static(const pipad_frame_t *frame, int32_t F, const float *const *X,
@@ -116,12 +116,11 @@ int pipad_frame_aggregate_static(const pipad_frame_t *frame, int32_t F, const fl
   size_t scratch_floats = 0;
   const int rc = pipad::static_scratch(&scratch_ptr, &scratch_floats);
   if (rc != PIPAD_OK) return rc;
-  return pipad::aggregate_launch(const_cast<pipad_frame *>(frame), F, X, ldx, Y, ldy,
-                                 static_cast<hipStream_t>(stream), nullptr, scratch_ptr,
-                                 scratch_floats);
+  return pipad::aggregate_launch(frame, F, X, ldx, Y, ldy, static_cast<hipStream_t>(stream),
+                                 pipad::ScratchRef{&scratch_ptr, &scratch_floats, true});
 }
 
-int pipad_frame_aggregate_update(const pipad_frame_t *frame, int32_t F, const float *const *X,
+int pipad_frame_aggregate_update(pipad_frame_t *frame, int32_t F, const float *const *X,
                                  int64_t ldx, const float *W, int64_t ldw, const float *bias,
                                  int32_t Fo, float *const *A, int64_t lda, float *const *H,
                                  int64_t ldh, void *stream) {
@@ -141,8 +140,8 @@ int pipad_frame_aggregate_update(const pipad_frame_t *frame, int32_t F, const fl
     if (dev != frame->device) return PIPAD_ERR_INVALID_ARG;
   }
   pipad::UpdateSpec u{W, ldw, bias, Fo, H, ldh};
-  return pipad::aggregate_launch(const_cast<pipad_frame *>(frame), F, X, ldx, A, A ? lda : F,
-                                 static_cast<hipStream_t>(stream), &u);
+  return pipad::aggregate_launch(frame, F, X, ldx, A, A ? lda : F, static_cast<hipStream_t>(stream),
+                                 pipad::ScratchRef{&frame->partial, &frame->partial_floats, false}, &u);
 }
 
 int pipad_frame_transpose(const pipad_frame_t *frame, pipad_alloc_fn alloc, void *alloc_ctx,
@@ -155,6 +154,22 @@ int pipad_frame_transpose(const pipad_frame_t *frame, pipad_alloc_fn alloc, void
   const int rc = pipad::transpose_frame(frame, alloc, alloc_ctx, static_cast<hipStream_t>(stream), &g);
   if (rc != PIPAD_OK) return rc;
   *out = g;
+  return PIPAD_OK;
+}
+
+int64_t pipad_recommended_row_stride(int32_t F) {
+  if (F < 1) return PIPAD_ERR_INVALID_ARG;
+  int64_t lines = ((int64_t)F * 4 + 127) / 128;  // 128-byte lines that hold a row
+  if (lines % 2 == 0) ++lines;                    // ... made odd
+  return lines * 32;
+}
+
+int pipad_frame_temporaries(pipad_frame_t *frame, void **ptr, size_t *bytes) {
+  if (!frame || !ptr || !bytes) return PIPAD_ERR_INVALID_ARG;
+  *ptr = frame->temp_ptr;
+  *bytes = frame->temp_bytes;
+  frame->temp_ptr = nullptr;
+  frame->temp_bytes = 0;
   return PIPAD_OK;
 }
 

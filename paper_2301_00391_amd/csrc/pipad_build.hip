@@ -995,6 +995,8 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   tmp.want(&dflags, (size_t)64);
   if (alloc) {
     temp = alloc(tmp.total, alloc_ctx);
+    f->temp_ptr = temp;
+    f->temp_bytes = temp ? tmp.total : 0;
   } else if (hipMalloc(&temp, tmp.total) != hipSuccess) {
     (void)hipGetLastError();
     temp = nullptr;

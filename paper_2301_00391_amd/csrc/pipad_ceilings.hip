@@ -85,8 +85,11 @@ int pipad_ceiling_stream_read(const float *src, size_t bytes, float *sink, void 
     return PIPAD_ERR_INVALID_ARG;
   if (bytes == 0) return PIPAD_OK;
   const size_t n16 = bytes / 16;
-  // 2048 workgroups: eight per CU, enough loads in flight to cover the memory latency
-  const unsigned blocks = (unsigned)std::min<size_t>(2048, (n16 + pipad::kBlock - 1) / pipad::kBlock);
+#ifndef PIPAD_STREAM_BLOCKS
+#define PIPAD_STREAM_BLOCKS 2048  // eight workgroups per CU
+#endif
+  const unsigned blocks =
+      (unsigned)std::min<size_t>(PIPAD_STREAM_BLOCKS, (n16 + pipad::kBlock - 1) / pipad::kBlock);
   hipLaunchKernelGGL(pipad::k_stream_read, dim3(blocks), dim3(pipad::kBlock), 0,
                      static_cast<hipStream_t>(stream), reinterpret_cast<const float4 *>(src), n16, sink);
   PIPAD_HIP(hipGetLastError());

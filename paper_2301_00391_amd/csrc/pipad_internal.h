@@ -52,6 +52,8 @@ struct pipad_frame {
   std::vector<void *> owned;         // everything to hipFree when own_memory
   pipad_alloc_fn alloc = nullptr;    // caller's allocator (also used for the aggregate scratch)
   void *alloc_ctx = nullptr;
+  void *temp_ptr = nullptr;          // the build's temporaries when they came from the caller's
+  size_t temp_bytes = 0;             // allocator (see pipad_frame_temporaries)
 
   int32_t nnz_c = 0;
   int32_t *rowptr_c = nullptr;       // [n+1]
@@ -210,14 +212,20 @@ struct UpdateSpec {
   float *const *H;    // k device pointers, row stride ldh
   int64_t ldh;
 };
-// Y may be null when `update` is given and the shape allows the fused kernel.
-// `fixed_scratch` (with its capacity in floats), when given, replaces the frame's own growable
-// scratch buffer: the call then allocates nothing and fails with PIPAD_ERR_SCRATCH when the
-// partial sums do not fit.
-int aggregate_launch(pipad_frame *f, int32_t F, const float *const *X, int64_t ldx,
-                     float *const *Y, int64_t ldy, hipStream_t stream,
-                     const UpdateSpec *update = nullptr, float *fixed_scratch = nullptr,
-                     size_t fixed_scratch_floats = 0);
+// Where the partial sums of a call go: a buffer and its capacity in floats.  `fixed`: the buffer
+// cannot grow (the call then allocates nothing and fails with PIPAD_ERR_SCRATCH when the partial
+// sums do not fit); otherwise it is the frame's own buffer, which the call may replace by a larger
+// one (through the frame's allocator).
+struct ScratchRef {
+  float **ptr;
+  size_t *floats;
+  bool fixed;
+};
+// Y may be null when `update` is given and the shape allows the fused kernel.  The frame itself
+// is only read.
+int aggregate_launch(const pipad_frame *f, int32_t F, const float *const *X, int64_t ldx,
+                     float *const *Y, int64_t ldy, hipStream_t stream, ScratchRef scratch,
+                     const UpdateSpec *update = nullptr);
 
 // Address, on the current device, of the library's fixed scratch array (resolved once per device).
 int static_scratch(float **ptr, size_t *floats);

@@ -148,6 +148,8 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
   tmp.want(&split_total, (size_t)PIPAD_MAX_K + 1);
   if (alloc) {
     temp = alloc(tmp.total, alloc_ctx);
+    g->temp_ptr = temp;
+    g->temp_bytes = temp ? tmp.total : 0;
   } else if (hipMalloc(&temp, tmp.total) != hipSuccess) {
     (void)hipGetLastError();
     temp = nullptr;
