@@ -5,11 +5,14 @@ S_per in {2, 4, 8} snapshots per partition over one-snapshot execution, against 
 against the feature dimension) and of its dimension-sensitivity test (Section 5.3, Fig. 11b),
 on the synthetic generator instead of the paper's datasets.
 
-  python -m paper_2301_00391_amd.sweeps overlap   # churn x k table
-  python -m paper_2301_00391_amd.sweeps features  # F x k table
-  python -m paper_2301_00391_amd.sweeps sliding   # cost per new snapshot when the frame slides by one
-  python -m paper_2301_00391_amd.sweeps workloads # the benchmark frames: one frame vs one snapshot at a time
-  python -m paper_2301_00391_amd.sweeps smallf    # F = 2 / 6 / 16: the coalescent kernel vs per-snapshot slices
+  python bench.py --sweep overlap    # churn x k table
+  python bench.py --sweep features   # F x k table
+  python bench.py --sweep sliding    # cost per new snapshot when the frame slides by one
+  python bench.py --sweep workloads  # the benchmark frames: one frame vs one snapshot at a time
+  python bench.py --sweep smallf     # F = 2 / 6 / 16: the coalescent kernel vs per-snapshot slices
+  python bench.py --sweep rows       # row-length classes: thresholds of the three kinds of work items
+  python bench.py --sweep labels     # the large frame with its nodes relabelled (locality sensitivity)
+  python bench.py --sweep oracle     # the CPU oracle on one thread and on all threads
 
 Every cell times ``pipad_frame_aggregate`` of one frame of k snapshots and, as the baseline, the
 same k snapshots aggregated one at a time (k frames of a single snapshot each, whose overlap part
@@ -45,17 +48,12 @@ def _frame_times(snaps, k, feat, dev, with_concatenated=False):
           for t in range(k)]
     frame = pipad.frame_build_overlap(gs)
     singles = [pipad.frame_build_overlap([g]) for g in gs]
-    layout_wide = False  # k separate matrices: the layout the slice-per-XCD kernel prefers
+    # k separate matrices (the layout the per-snapshot slices prefer)
     xw = torch.rand((n, k, feat), device=dev) * 2 - 1
-    if layout_wide:
-        x, y = xw, torch.empty_like(xw)
-        xs = [xw[:, t:t + 1, :] for t in range(k)]
-        ys = [y[:, t:t + 1, :] for t in range(k)]
-    else:
-        x = [xw[:, t, :].contiguous() for t in range(k)]
-        y = [torch.empty_like(v) for v in x]
-        xs = [[v] for v in x]
-        ys = [[v] for v in y]
+    x = [xw[:, t, :].contiguous() for t in range(k)]
+    y = [torch.empty_like(v) for v in x]
+    xs = [[v] for v in x]
+    ys = [[v] for v in y]
     t_frame = _time(lambda: pipad.frame_aggregate(frame, x, y))
 
     def one_by_one():
@@ -121,9 +119,13 @@ def sliding_sweep(dev):
     the whole frame again; only the entering snapshot, as a frame of its own; or - when the
     snapshots are known in advance, as in training - disjoint groups of k snapshots aggregated as
     frames once, cost divided by k."""
-    print("cost per new snapshot in ms (build_overlap + aggregate), stride-1 frames\n")
-    print("| workload | whole frame again | entering snapshot alone | disjoint groups of k, per snapshot |")
-    print("|---|---|---|---|")
+    print("cost per new snapshot in ms, stride-1 frames: build_overlap + aggregate for the first three "
+          "columns; extraction only for the last two\n")
+    print("| workload | whole frame again | whole extraction, aggregation of the entering snapshot "
+          "(pipad_frame_aggregate_subset) | entering snapshot alone as a frame of one | "
+          "disjoint groups of k, per snapshot | extraction of the whole frame | "
+          "lower bound of an incremental extraction |")
+    print("|---|---|---|---|---|---|---|")
     for name in ("small", "medium"):
         cfg = synth.CONFIGS[name]
         n, k, feat = cfg.n, cfg.k, cfg.feat
@@ -138,6 +140,12 @@ def sliding_sweep(dev):
                 fr = pipad.frame_build_overlap(gs[f:f + k])
                 pipad.frame_aggregate(fr, xs[f:f + k], ys[f:f + k])
 
+        def subset():
+            for f in range(cfg.frames):
+                fr = pipad.frame_build_overlap(gs[f:f + k])
+                pipad.frame_aggregate_subset(fr, [k - 1], [None] * (k - 1) + [xs[f + k - 1]],
+                                             [None] * (k - 1) + [ys[f + k - 1]])
+
         def entering():
             for f in range(cfg.frames):
                 t = f + k - 1
@@ -149,11 +157,35 @@ def sliding_sweep(dev):
                 fr = pipad.frame_build_overlap(gs[g * k:(g + 1) * k])
                 pipad.frame_aggregate(fr, xs[g * k:(g + 1) * k], ys[g * k:(g + 1) * k])
 
+        # An incremental extraction (Section 3.3 reuse applied to the topology): the k - 1 kept
+        # snapshots share M = C + R, R = the entries missing only from the leaving snapshot, and
+        # the next frame follows from one split of M against the entering snapshot.  Its first two
+        # steps can be run with the existing call: (1) R and the exclusive parts without R =
+        # extraction over the k - 1 kept exclusive parts; (2) the split of M (here: C, a few
+        # entries fewer) against the entering snapshot = extraction of a frame of two.  The merges
+        # that turn the pieces back into canonical parts come on top, so this is a lower bound.
+        def build_only():
+            for f in range(cfg.frames):
+                pipad.frame_build_overlap(gs[f:f + k])
+
+        frames0 = [pipad.frame_build_overlap(gs[f:f + k]) for f in range(cfg.frames - 1)]
+        parts = [([fr.delta(t) for t in range(1, k)], fr.common()) for fr in frames0]
+
+        def incremental():
+            for f, (deltas, common) in enumerate(parts):
+                pipad.frame_build_overlap(deltas)
+                pipad.frame_build_overlap([common, gs[f + k]])
+
         t_whole = _time(whole, 3) / cfg.frames
+        t_subset = _time(subset, 3) / cfg.frames
         t_enter = _time(entering, 3) / cfg.frames
         t_group = _time(groups, 3) / (cfg.snapshots // k * k)
+        t_build = _time(build_only, 3) / cfg.frames
+        t_incr = _time(incremental, 3) / len(parts)
         print(f"| {name} (N = {n}, k = {k}, F = {feat}, {cfg.frames} frames) | {t_whole:.3f} | "
-              f"{t_enter:.3f} | {t_group:.3f} |", flush=True)
+              f"{t_subset:.3f} | {t_enter:.3f} | {t_group:.3f} | {t_build:.3f} | {t_incr:.3f} |", flush=True)
+        for fr in frames0:
+            fr.close()
 
 
 def workload_sweep(dev):
@@ -225,6 +257,105 @@ def small_f_sweep(dev):
         frame.close()
 
 
+def row_class_sweep(dev):
+    """Load balance by row length (the job of the paper's sliced CSR, Section 4.1 / 5.4): the
+    thresholds between the three kinds of work items on the large frame."""
+    cfg = synth.CONFIGS["large"]
+    n, k, feat = cfg.n, cfg.k, cfg.feat
+    snaps = synth.graphs(n, cfg.edges, k, cfg.churn, cfg.model, cfg.params, cfg.seed)
+    gs = [(torch.from_numpy(snaps.rowptr[t]).to(dev), torch.from_numpy(snaps.col[t]).to(dev))
+          for t in range(k)]
+    stride = pipad.padded_row_stride(feat)
+    xb = [torch.rand((n, stride), device=dev) * 2 - 1 for _ in range(k)]
+    xs = [b[:, :feat] for b in xb]
+    ys = [torch.empty((n, feat), device=dev) for _ in range(k)]
+    defaults = {key: pipad.get_option(key) for key in
+                ("short_max", "mid_max", "hub_threshold", "hub_segment", "sub_classes")}
+    print("large frame (N = 1M R-MAT, k = 8, F = 64), ms per call\n")
+    print("| short_max | mid_max | hub_threshold = hub_segment | sub_classes | extraction | aggregation |")
+    print("|---|---|---|---|---|---|")
+    rows = [dict(), dict(short_max=32), dict(short_max=128), dict(mid_max=256), dict(mid_max=1024),
+            dict(mid_max=2048), dict(hub_threshold=8192, hub_segment=8192),
+            dict(hub_threshold=1 << 30, hub_segment=1 << 30), dict(sub_classes=2), dict(sub_classes=4),
+            dict(mid_max=1 << 30)]
+    for change in rows:
+        opts = dict(defaults, **change)
+        for key, val in opts.items():
+            pipad.set_option(key, val)
+        t_build = _time(lambda: pipad.frame_build_overlap(gs), 3)
+        frame = pipad.frame_build_overlap(gs)
+        t_agg = _time(lambda: pipad.frame_aggregate(frame, xs, ys))
+        frame.close()
+        seg = "never cut" if opts["hub_threshold"] >= 1 << 30 else str(opts["hub_threshold"])
+        mid = "all rows whole (no column classes)" if opts["mid_max"] >= 1 << 30 else str(opts["mid_max"])
+        print(f"| {opts['short_max']} | {mid} | {seg} | {opts['sub_classes']} | {t_build:.3f} | {t_agg:.3f} |",
+              flush=True)
+    for key, val in defaults.items():
+        pipad.set_option(key, val)
+
+
+def label_sweep(dev):
+    """Locality sensitivity: the large frame with its nodes relabelled (graph and features permuted
+    together, so the result is the same up to the permutation)."""
+    cfg = synth.CONFIGS["large"]
+    n, k, feat = cfg.n, cfg.k, cfg.feat
+    snaps = synth.graphs(n, cfg.edges, k, cfg.churn, cfg.model, cfg.params, cfg.seed)
+    deg = np.diff(snaps.rowptr[0])
+    rng = np.random.default_rng(0)
+    perms = {"natural ids (R-MAT: popularity tied to the id's bits)": None,
+             "random ids": rng.permutation(n).astype(np.int64),
+             "ids sorted by degree (hubs first)": np.argsort(np.argsort(-deg, kind="stable"), kind="stable")}
+    stride = pipad.padded_row_stride(feat)
+    print("large frame (N = 1M R-MAT, k = 8, F = 64), aggregation ms per call\n")
+    print("| node labels | rows of X padded (stride 96 floats) | rows of X dense (stride 64) |")
+    print("|---|---|---|")
+    for label, new_id in perms.items():
+        gs = []
+        for t in range(k):
+            rp, col = snaps.rowptr[t], snaps.col[t]
+            if new_id is not None:  # entry (i, j) -> (new_id[i], new_id[j]), rows and columns re-sorted
+                rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(rp))
+                r2, c2 = new_id[rows], new_id[col]
+                order = np.lexsort((c2, r2))
+                rp = np.concatenate([[0], np.cumsum(np.bincount(r2, minlength=n))]).astype(np.int32)
+                col = c2[order].astype(np.int32)
+            gs.append((torch.from_numpy(np.ascontiguousarray(rp)).to(dev),
+                       torch.from_numpy(np.ascontiguousarray(col)).to(dev)))
+        frame = pipad.frame_build_overlap(gs)
+        cells = []
+        for st in (stride, feat):
+            xb = [torch.rand((n, st), device=dev) * 2 - 1 for _ in range(k)]
+            xs = [b[:, :feat] for b in xb]
+            ys = [torch.empty((n, feat), device=dev) for _ in range(k)]
+            cells.append(_time(lambda: pipad.frame_aggregate(frame, xs, ys)))
+            del xb, xs, ys
+        frame.close()
+        print(f"| {label} | {cells[0]:.3f} | {cells[1]:.3f} |", flush=True)
+
+
+def oracle_sweep(dev):
+    """The CPU oracle (plain per-snapshot aggregation in double, never tuned) on this host: one
+    thread and all hardware threads, one snapshot of every benchmark frame."""
+    import time
+
+    import oracle
+    print("CPU oracle, one snapshot, seconds and edge*feat updates per second\n")
+    print("| workload | threads | seconds | updates/s |")
+    print("|---|---|---|---|")
+    for name in ("medium", "large", "low-overlap"):
+        cfg = synth.CONFIGS[name]
+        snaps = synth.graphs(cfg.n, cfg.edges, 1, cfg.churn, cfg.model, cfg.params, cfg.seed)
+        rows, cols = snaps.coo(0)
+        x = synth.features(cfg.seed, 0, cfg.n, cfg.feat)
+        upd = cfg.feat * (cols.size + cfg.n)
+        for threads in (1, oracle.hardware_threads()):
+            t0 = time.perf_counter()
+            _, _, _, used = oracle.aggregate(cfg.n, rows, cols, x, threads=threads,
+                                             want_bound=False, want_double=False)
+            dt = time.perf_counter() - t0
+            print(f"| {name} | {used} | {dt:.2f} | {upd / dt:.3g} |", flush=True)
+
+
 def main(argv):
     if not torch.cuda.is_available():
         print("sweeps need a GPU", file=sys.stderr)
@@ -241,6 +372,12 @@ def main(argv):
         workload_sweep(dev)
     elif which == "smallf":
         small_f_sweep(dev)
+    elif which == "rows":
+        row_class_sweep(dev)
+    elif which == "labels":
+        label_sweep(dev)
+    elif which == "oracle":
+        oracle_sweep(dev)
     else:
         print(__doc__, file=sys.stderr)
         return 2

@@ -154,6 +154,23 @@ int pipad_frame_shape(const pipad_frame_t *frame, int32_t *n, int32_t *k);
 int pipad_frame_aggregate(pipad_frame_t *frame, int32_t F, const float *const *X, int64_t ldx,
                           float *const *Y, int64_t ldy, void *stream);
 
+/* pipad_frame_aggregate for some of the frame's snapshots only: the inter-frame reuse of Section
+ * 3.3 ("opportunities for data reuse") and Section 4.4 ("inter-frame reuse").  When the frame
+ * slides by one snapshot, k - 1 of its snapshots were already part of the previous frame, and an
+ * aggregation whose input does not depend on the weights (the first layer's) has the same result
+ * for them as before: the caller keeps those Y_t and asks for the entering snapshot alone, while
+ * later layers call pipad_frame_aggregate on the same frame for all k.
+ *   nsel, snapshots   host array of nsel distinct snapshot numbers in [0, k), taken in this order;
+ *                     nsel = 0 does nothing
+ *   X, Y              host arrays of k device pointers as for pipad_frame_aggregate; only the
+ *                     entries of the chosen snapshots are looked at (the others may be NULL)
+ * Every chosen Y[t] gets exactly the bits pipad_frame_aggregate would give it.  Other rules
+ * (device, stream, scratch, determinism) as for pipad_frame_aggregate; operands of F < 32 take
+ * the per-snapshot kernel here, never the coalescent one. */
+int pipad_frame_aggregate_subset(pipad_frame_t *frame, int32_t nsel, const int32_t *snapshots,
+                                 int32_t F, const float *const *X, int64_t ldx, float *const *Y,
+                                 int64_t ldy, void *stream);
+
 /* pipad_frame_aggregate for callers that cannot allocate device memory: code under HIP graph
  * (stream) capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
  * kernels and bit-identical results, but the partial sums of split rows go to a fixed array of

@@ -3,7 +3,7 @@
 The compute lives in ``libpipad.so`` (sources under ``csrc/``, contract in ``include/pipad.h``);
 this package is the thin binding.  There is no CPU fallback.
 """
-from .binding import (Frame, PipadError, frame_aggregate, frame_aggregate_update,
+from .binding import (Frame, PipadError, frame_aggregate, frame_aggregate_subset, frame_aggregate_update,
                       frame_build_overlap, frame_transpose, get_option, load_library,
                       set_option)
 
@@ -24,5 +24,5 @@ def padded_row_stride(feat: int) -> int:
     return stride
 
 
-__all__ = ["Frame", "PipadError", "frame_aggregate", "frame_aggregate_update", "frame_build_overlap", "frame_transpose", "get_option",
+__all__ = ["Frame", "PipadError", "frame_aggregate", "frame_aggregate_subset", "frame_aggregate_update", "frame_build_overlap", "frame_transpose", "get_option",
            "set_option", "load_library", "coalescent_row_bytes", "padded_row_stride"]

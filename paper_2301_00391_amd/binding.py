@@ -50,6 +50,8 @@ SIGNATURES = {
     "pipad_frame_shape": (ctypes.c_int, [_vp, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]),
     "pipad_frame_aggregate": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_vp), _i64,
                                              ctypes.POINTER(_vp), _i64, _vp]),
+    "pipad_frame_aggregate_subset": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_i32), _i32,
+                                                    ctypes.POINTER(_vp), _i64, ctypes.POINTER(_vp), _i64, _vp]),
     "pipad_frame_aggregate_static": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_vp), _i64,
                                                     ctypes.POINTER(_vp), _i64, _vp]),
     "pipad_frame_aggregate_update": (ctypes.c_int, [_vp, _i32, ctypes.POINTER(_vp), _i64, _vp, _i64,
@@ -332,6 +334,41 @@ def frame_aggregate(frame: Frame, X: Features, Y: Optional[Features] = None, str
         fn = lib.pipad_frame_aggregate_static if static_scratch else lib.pipad_frame_aggregate
         _check(fn(frame._h, F, xa, ldx, ya, ldy, _stream_handle(stream)))
     return Y
+
+
+def frame_aggregate_subset(frame: Frame, snapshots: Sequence[int], X: Sequence[Optional[torch.Tensor]],
+                           Y: Sequence[Optional[torch.Tensor]], stream=None) -> None:
+    """pipad_frame_aggregate_subset: Y[t] = D_t^-1/2 (A_t + I) D_t^-1/2 X[t] for the listed snapshots
+    of the frame only (inter-frame reuse: the other Y_t are kept from the previous frame).  X and Y
+    are lists of k entries; those of snapshots not listed may be None."""
+    lib = load_library()
+    n, k = frame.n, frame.k
+    sel = [int(t) for t in snapshots]
+    if not sel:
+        return
+    if len(X) != k or len(Y) != k:
+        raise ValueError("X and Y must have k entries")
+    F, ldx, ldy = None, None, None
+    xa, ya = (_vp * k)(), (_vp * k)()
+    for t in sel:
+        for m, name in ((X[t], "X"), (Y[t], "Y")):
+            if m is None or m.dtype != torch.float32 or not m.is_cuda or m.dim() != 2 or m.shape[0] != n:
+                raise ValueError(f"{name}[{t}] must be a float32 [n, F] matrix on the GPU")
+            if m.shape[1] > 1 and m.stride(1) != 1:
+                raise ValueError("feature columns must be contiguous")
+        if F is None:
+            F = int(X[t].shape[1])
+            ldx = int(X[t].stride(0)) if n > 1 else max(int(X[t].stride(0)), F)
+            ldy = int(Y[t].stride(0)) if n > 1 else max(int(Y[t].stride(0)), F)
+        if X[t].shape[1] != F or Y[t].shape[1] != F or (n > 1 and (X[t].stride(0) != ldx or Y[t].stride(0) != ldy)):
+            raise ValueError("the chosen matrices must share their shape and row strides")
+        xa[t], ya[t] = X[t].data_ptr(), Y[t].data_ptr()
+    arr = (_i32 * len(sel))(*sel)
+    frame._release_temporaries()
+    frame._streams.add(stream if stream is not None else torch.cuda.current_stream(frame.device))
+    with torch.cuda.device(frame.device):
+        _check(lib.pipad_frame_aggregate_subset(frame._h, len(sel), arr, F, xa, ldx, ya, ldy,
+                                                _stream_handle(stream)))
 
 
 def frame_aggregate_update(frame: Frame, X: Features, W: torch.Tensor,

@@ -71,6 +71,8 @@ struct AggArgs {
   int32_t ls_log2;    // log2 of the lanes per slice row
   int32_t fchunks;    // slices per snapshot = ceil(F / (LS * VEC))
   int32_t nslices;    // k * fchunks
+  int32_t nsel;       // snapshots this call aggregates (k, or fewer for a subset call)
+  uint64_t sel[4];    // their numbers, one byte each, in the order they are taken
   int32_t n_short, n_long, n_items, n_hub;
   // workgroups of one slice ("phase"): for every sub class in turn 8 * blocks_wide for the hub
   // units (workgroup r of them takes XCD r mod 8's class), then blocks_mid for the mid rows, then
@@ -380,6 +382,14 @@ __device__ __forceinline__ void reduce_slots(int ls_log2, typename V<VEC>::T &ac
 
 constexpr bool kPartialNt = PIPAD_PARTIAL_NT;  // non-temporal stores for the partial sums
 
+// The t_seq-th snapshot this call aggregates (all four words are read before one is chosen, so
+// that the kernel arguments are only read at constant offsets).
+__device__ __forceinline__ int selected_snapshot(const AggArgs &a, int t_seq) {
+  const uint64_t w0 = a.sel[0], w1 = a.sel[1], w2 = a.sel[2], w3 = a.sel[3];
+  const uint64_t w = t_seq < 8 ? w0 : t_seq < 16 ? w1 : t_seq < 24 ? w2 : w3;
+  return (int)((w >> ((t_seq & 7) * 8)) & 0xffu);
+}
+
 // Where partial sum `slot` (= hub unit * nclass + class) of a slice goes: all partial sums of one
 // slice are contiguous, so a phase writes and the finishing kernel reads dense memory.
 __device__ __forceinline__ float *partial_slot(const AggArgs &a, int slice, int64_t slot, int fl, int vec) {
@@ -431,7 +441,7 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
   const int slice_seq = (int)(b / a.blocks_per_phase);
   int64_t w = b - slice_seq * a.blocks_per_phase;
   const int t_seq = slice_seq / a.fchunks;
-  const int slice = (slice_seq - t_seq * a.fchunks) * a.k + t_seq;
+  const int slice = (slice_seq - t_seq * a.fchunks) * a.k + selected_snapshot(a, t_seq);
   const Slice s = slice_setup(a, slice, fl, VEC);
   const bool ntl = a.nt & 2;
 
@@ -606,8 +616,10 @@ __global__ __launch_bounds__(kBlock) void k_split_finish(const AggArgs a) {
   const int nteams = kWave >> a.ls_log2;
   const int64_t row_blocks = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock;
   const int64_t b = blockIdx.x;
-  const int slice = (int)(b / row_blocks);
-  const int64_t sr = (b - slice * row_blocks) * kWavesPerBlock + wave;
+  const int slice_seq = (int)(b / row_blocks);
+  const int t_seq = slice_seq / a.fchunks;
+  const int slice = (slice_seq - t_seq * a.fchunks) * a.k + selected_snapshot(a, t_seq);
+  const int64_t sr = (b - slice_seq * row_blocks) * kWavesPerBlock + wave;
   if (sr >= a.n_hub) return;
   const Slice s = slice_setup(a, slice, fl, VEC);
   const int32_t i = a.hub_rows[sr];
@@ -1020,9 +1032,10 @@ inline size_t update_lds_bytes(const AggArgs &a) {
 
 template <int VEC>
 int launch(const AggArgs &a, bool fast, hipStream_t st, bool fused_update = false) {
-  const int64_t blocks = a.blocks_per_phase * a.nslices;
+  const int64_t phases = (int64_t)a.nsel * a.fchunks;
+  const int64_t blocks = a.blocks_per_phase * phases;
   if (blocks >= ((int64_t)1 << 31)) return PIPAD_ERR_TOO_LARGE;
-  const int64_t fin = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock * a.nslices;
+  const int64_t fin = ((int64_t)a.n_hub + kWavesPerBlock - 1) / kWavesPerBlock * phases;
   if (fin >= ((int64_t)1 << 31)) return PIPAD_ERR_TOO_LARGE;
   const dim3 grid((unsigned)blocks), block(kBlock);
   if constexpr (VEC == 4) {
@@ -1098,8 +1111,8 @@ int static_scratch(float **ptr, size_t *floats) {
 
 int aggregate_launch(const pipad_frame *f, int32_t F, const float *const *X, int64_t ldx,
                      float *const *Y, int64_t ldy, hipStream_t st, ScratchRef scratch,
-                     const UpdateSpec *upd) {
-  if (f->n == 0) return PIPAD_OK;
+                     const UpdateSpec *upd, const int32_t *subset, int32_t nsubset) {
+  if (f->n == 0 || (subset && nsubset == 0)) return PIPAD_OK;
   const Options &opt = f->opt;  // as they stood when the frame was built
   AggArgs a;
   std::memset(&a, 0, sizeof(a));
@@ -1131,6 +1144,9 @@ int aggregate_launch(const pipad_frame *f, int32_t F, const float *const *X, int
   a.n_items = f->n_items;
   a.n_hub = f->n_hub;
   a.nt = (int32_t)opt.agg_nt;
+  a.nsel = subset ? nsubset : f->k;
+  for (int q = 0; q < a.nsel; ++q)
+    a.sel[q >> 3] |= (uint64_t)(subset ? subset[q] : q) << ((q & 7) * 8);
   bool vec4 = F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
   for (int t = 0; t < f->k; ++t) {
     a.rowptr_d[t] = f->rowptr_d[t];
@@ -1138,7 +1154,7 @@ int aggregate_launch(const pipad_frame *f, int32_t F, const float *const *X, int
     a.wc[t] = f->wc[t];
     a.wd[t] = f->wd[t];
     a.swc[t] = f->swc[t];
-    a.X[t] = X[t];
+    a.X[t] = X[t];  // (null for a snapshot a subset call leaves out: never touched)
     a.Y[t] = Y ? Y[t] : nullptr;
     if ((reinterpret_cast<uintptr_t>(X[t]) | reinterpret_cast<uintptr_t>(a.Y[t])) & 15u) vec4 = false;
   }
@@ -1164,7 +1180,7 @@ int aggregate_launch(const pipad_frame *f, int32_t F, const float *const *X, int
   // XCDs would fetch the same lines); only operands of a few hundred KB are a tie.
   const int64_t mode = opt.agg_coalescent;  // 0 never, 1 automatic, 2 whenever possible
   const bool wanted = mode >= 2 || (mode == 1 && (int64_t)f->n * f->k * F * 4 >= ((int64_t)1 << 20));
-  bool coalescent = wanted && !upd && F < 32 && f->k > 1 && ldx >= (int64_t)f->k * F &&
+  bool coalescent = wanted && !upd && !subset && F < 32 && f->k > 1 && ldx >= (int64_t)f->k * F &&
                     ldy >= (int64_t)f->k * F && (int64_t)f->n * ldx * 4 < ((int64_t)1 << 32);
   for (int t = 1; t < f->k && coalescent; ++t)
     coalescent = X[t] == X[0] + (int64_t)t * F && Y[t] == Y[0] + (int64_t)t * F;

@@ -100,6 +100,37 @@ int pipad_frame_aggregate(pipad_frame_t *frame, int32_t F, const float *const *X
                                  pipad::ScratchRef{&frame->partial, &frame->partial_floats, false});
 }
 
+int pipad_frame_aggregate_subset(pipad_frame_t *frame, int32_t nsel, const int32_t *snapshots,
+                                 int32_t F, const float *const *X, int64_t ldx, float *const *Y,
+                                 int64_t ldy, void *stream) {
+  if (!frame || !X || !Y || F < 1 || ldx < F || ldy < F || nsel < 0 || nsel > frame->k ||
+      (nsel > 0 && !snapshots))
+    return PIPAD_ERR_INVALID_ARG;
+  uint32_t seen = 0;
+  for (int q = 0; q < nsel; ++q) {
+    const int32_t t = snapshots[q];
+    if (t < 0 || t >= frame->k || (seen >> t & 1u)) return PIPAD_ERR_INVALID_ARG;
+    seen |= 1u << t;
+    if (frame->n > 0 && (!X[t] || !Y[t])) return PIPAD_ERR_INVALID_ARG;
+  }
+  if ((int64_t)frame->n * ldx >= ((int64_t)1 << 40) || (int64_t)frame->n * ldy >= ((int64_t)1 << 40))
+    return PIPAD_ERR_TOO_LARGE;
+  if (frame->n == 0 || nsel == 0) return PIPAD_OK;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return pipad::hip_fail(hipGetLastError(), "hipGetDevice");
+  if (dev != frame->device) return PIPAD_ERR_INVALID_ARG;
+  // the aggregation only ever looks at the pointers of the chosen snapshots
+  const float *xs[PIPAD_MAX_K] = {};
+  float *ys[PIPAD_MAX_K] = {};
+  for (int q = 0; q < nsel; ++q) {
+    xs[snapshots[q]] = X[snapshots[q]];
+    ys[snapshots[q]] = Y[snapshots[q]];
+  }
+  return pipad::aggregate_launch(frame, F, xs, ldx, ys, ldy, static_cast<hipStream_t>(stream),
+                                 pipad::ScratchRef{&frame->partial, &frame->partial_floats, false},
+                                 nullptr, snapshots, nsel);
+}
+
 int pipad_frame_aggregate_static(const pipad_frame_t *frame, int32_t F, const float *const *X,
                                  int64_t ldx, float *const *Y, int64_t ldy, void *stream) {
   if (!frame || !X || !Y || F < 1 || ldx < F || ldy < F) return PIPAD_ERR_INVALID_ARG;

@@ -551,8 +551,8 @@ struct SplitArgs {
   const int32_t *item_row, *item_v0, *item_v1;
   const int32_t *rowptr[PIPAD_MAX_K + 1];  // parts: common, then exclusive
   const int32_t *col[PIPAD_MAX_K + 1];
-  const float *wc[PIPAD_MAX_K];            // canonical scales of the overlap part
-  const float *wd[PIPAD_MAX_K];            // and of the exclusive parts
+  const float *dinv_nk;                    // [n][k]
+  const float *wd[PIPAD_MAX_K];            // canonical scales of the exclusive parts
   uint32_t *ulen;                          // [(k + 1) * n_units + 1]: lengths, then (scanned) starts
   uint32_t *sptr;
   int32_t *scol;
@@ -647,20 +647,7 @@ __device__ inline void split_fill_part(const SplitArgs &g, int p, int32_t u, int
       }
     }
     if (p == 0) {
-      // the scales of 8 snapshots at a time: all loads go out before the first store
-      for (int t0 = 0; t0 < g.k; t0 += 8) {
-        float wv[8][UN];
-#pragma unroll
-        for (int tt = 0; tt < 8; ++tt)
-#pragma unroll
-          for (int j = 0; j < UN; ++j)
-            wv[tt][j] = (t0 + tt < g.k && cv[j] >= 0) ? g.wc[t0 + tt][base + j * tl + q] : 0.f;
-#pragma unroll
-        for (int tt = 0; tt < 8; ++tt)
-#pragma unroll
-          for (int j = 0; j < UN; ++j)
-            if (t0 + tt < g.k && cv[j] >= 0) g.swc[t0 + tt][pos[j]] = wv[tt][j];
-      }
+      // (the k scales of an overlap entry follow in k_split_scales, one lane per grouped entry)
     } else {
       float wv[UN];
 #pragma unroll
@@ -672,6 +659,22 @@ __device__ inline void split_fill_part(const SplitArgs &g, int p, int32_t u, int
 #pragma unroll
     for (int j = 0; j < UN; ++j)
       if (cv[j] >= 0) g.scol[pos[j]] = cv[j];
+  }
+}
+
+// Column scales of the grouped overlap entries: swc[t][e] = dinv_t[scol[e]], one lane per entry,
+// a node's k scales from the node-major copy of D^-1/2 (one line per node).
+__global__ __launch_bounds__(kBlock) void k_split_scales(SplitArgs g) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e >= g.total_c) return;
+  const float *row = g.dinv_nk + (int64_t)g.scol[e] * g.k;
+  if ((g.k & 3) == 0) {
+    for (int t = 0; t < g.k; t += 4) {
+      const float4 w4 = *reinterpret_cast<const float4 *>(row + t);
+      g.swc[t][e] = w4.x; g.swc[t + 1][e] = w4.y; g.swc[t + 2][e] = w4.z; g.swc[t + 3][e] = w4.w;
+    }
+  } else {
+    for (int t = 0; t < g.k; ++t) g.swc[t][e] = row[t];
   }
 }
 
@@ -879,10 +882,10 @@ int build_split_arrays(pipad_frame *f, uint32_t *ulen, uint32_t *bsum, hipStream
   g.item_v1 = f->item_v1;
   g.rowptr[0] = f->rowptr_c;
   g.col[0] = f->col_c;
+  g.dinv_nk = f->dinv_nk;
   for (int t = 0; t < f->k; ++t) {
     g.rowptr[1 + t] = f->rowptr_d[t];
     g.col[1 + t] = f->col_d[t];
-    g.wc[t] = f->wc[t];
     g.wd[t] = f->wd[t];
     g.swc[t] = f->swc[t];
   }
@@ -901,6 +904,8 @@ int build_split_arrays(pipad_frame *f, uint32_t *ulen, uint32_t *bsum, hipStream
   }
   auto fill = f->sub_log2 == 0 ? k_split_fill<8> : f->sub_log2 == 1 ? k_split_fill<16> : k_split_fill<32>;
   hipLaunchKernelGGL(fill, grid1(f->n_units, kWavesPerBlock), dim3(kBlock), 0, st, g);
+  if (g.total_c > 0)
+    hipLaunchKernelGGL(k_split_scales, grid1(g.total_c, kBlock), dim3(kBlock), 0, st, g);
   PIPAD_HIP(hipGetLastError());
   return PIPAD_OK;
 }

@@ -223,9 +223,12 @@ struct ScratchRef {
 };
 // Y may be null when `update` is given and the shape allows the fused kernel.  The frame itself
 // is only read.
+// `subset` (nsubset distinct snapshot numbers): only these snapshots are aggregated; X[t] and Y[t]
+// of the others may be null.
 int aggregate_launch(const pipad_frame *f, int32_t F, const float *const *X, int64_t ldx,
                      float *const *Y, int64_t ldy, hipStream_t stream, ScratchRef scratch,
-                     const UpdateSpec *update = nullptr);
+                     const UpdateSpec *update = nullptr, const int32_t *subset = nullptr,
+                     int32_t nsubset = 0);
 
 // Address, on the current device, of the library's fixed scratch array (resolved once per device).
 int static_scratch(float **ptr, size_t *floats);

@@ -638,3 +638,72 @@ def test_randomised_frames(pipad, seed):
     pipad.set_option("sub_classes", int(rng.choice([1, 2, 4])))
     F = int(rng.choice([1, 4, 7, 16, 64, 96]))
     run_case(pipad, n, lists, F, seed=seed, layout="list" if seed % 2 else "wide")
+
+
+# ---- sliding frames: inter-frame reuse of first-layer aggregation results ---------------------
+@pytest.mark.parametrize("name", ["small", "medium"])
+def test_sliding_frames_with_cached_results(pipad, name):
+    """Section 3.3 / 4.4: when the frame slides by one snapshot, the first layer's aggregation of
+    the k - 1 kept snapshots is unchanged.  Every slid frame of the workload is built; the entering
+    snapshot alone is aggregated (pipad_frame_aggregate_subset) into a cache of per-snapshot
+    results.  What the subset call writes must equal, bit for bit, what a full aggregation of the
+    same frame gives for that snapshot; the results kept from earlier frames were summed in another
+    order (an entry may sit in the overlap part of one frame and in an exclusive part of the next),
+    so they agree with the full aggregation within twice the parity bound, and every cached result
+    is checked against the oracle itself."""
+    cfg = synth.CONFIGS[name]
+    s = synth.make(cfg)
+    n, k, F = cfg.n, cfg.k, cfg.feat
+    dev = "cuda:0"
+    gs = to_gpu_snapshots(torch, s, range(cfg.snapshots))
+    Xh = [synth.features(cfg.seed, t, n, F) for t in range(cfg.snapshots)]
+    X = [torch.from_numpy(x).to(dev) for x in Xh]
+    cache = [None] * cfg.snapshots
+    for f in range(cfg.frames):
+        frame = pipad.frame_build_overlap(gs[f:f + k])
+        if f < 2:  # the decomposition of a slid frame is as exact as any other
+            check_overlap(frame, oracle.overlap(n, [s.coo(t) for t in range(f, f + k)]))
+        new = list(range(k)) if f == 0 else [k - 1]
+        ys = [None] * k
+        for j in new:
+            cache[f + j] = torch.full((n, F), float("nan"), device=dev)
+            ys[j] = cache[f + j]
+        pipad.frame_aggregate_subset(frame, new, [X[f + j] if j in new else None for j in range(k)], ys)
+        full = pipad.frame_aggregate(frame, X[f:f + k])
+        torch.cuda.synchronize()
+        for j in new:
+            assert torch.equal(full[j], cache[f + j]), f"frame {f}, snapshot {f + j}"
+        kept = [j for j in range(k) if j not in new]
+        if kept:
+            worst = max(float((full[j] - cache[f + j]).abs().max()) for j in kept)
+            assert worst < 1e-4, f"frame {f}: kept results drifted by {worst}"
+        frame.close()
+    for t in range(cfg.snapshots):
+        rows, cols = s.coo(t)
+        _, yd, bound, _ = oracle.aggregate(n, rows, cols, Xh[t], threads=8)
+        check_y(cache[t].cpu().numpy(), yd, bound, f"cached snapshot {t}")
+
+
+def test_subset_arguments(pipad):
+    import ctypes
+    rng = np.random.default_rng(3)
+    n, k, F = 120, 4, 8
+    lists = churned(rng, n, k, 0.05, 0.8)
+    snaps = [(torch.from_numpy(rp).cuda(), torch.from_numpy(c).cuda()) for rp, c in lists]
+    frame = pipad.frame_build_overlap(snaps)
+    X = [torch.rand((n, F), device="cuda:0") for _ in range(k)]
+    Y = [torch.full((n, F), 5.0, device="cuda:0") for _ in range(k)]
+    lib = pipad.load_library()
+    xp = (ctypes.c_void_p * k)(*[x.data_ptr() for x in X])
+    yp = (ctypes.c_void_p * k)(*[y.data_ptr() for y in Y])
+    st = torch.cuda.current_stream().cuda_stream
+    for bad in ([0, 0], [4], [-1], [0, 1, 2, 3, 0]):
+        arr = (ctypes.c_int32 * len(bad))(*bad)
+        assert lib.pipad_frame_aggregate_subset(frame._h, len(bad), arr, F, xp, F, yp, F, st) == -1
+    # snapshots 2 and 0, in that order; 1 and 3 are left alone
+    pipad.frame_aggregate_subset(frame, [2, 0], X, Y)
+    full = pipad.frame_aggregate(frame, X)
+    torch.cuda.synchronize()
+    assert torch.equal(Y[2], full[2]) and torch.equal(Y[0], full[0])
+    assert torch.all(Y[1] == 5.0) and torch.all(Y[3] == 5.0)
+    frame.close()
