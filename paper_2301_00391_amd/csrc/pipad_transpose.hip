@@ -1,13 +1,66 @@
 // pipad_frame_transpose: the frame of the transposed parts with the forward normalisation.
-// A translation unit of its own, so that the library sort it uses is only loaded when it is called.
+//
+// Every part (the overlap part and the k exclusive parts) is transposed on its own - the transpose
+// of an intersection is the intersection of the transposes - and all 1 + k parts go through the
+// same launches.  Transposing a CSR pattern is a stable sort of its entries by column: rows arrive
+// in ascending order, so they leave in ascending order within every column, which makes the result
+// canonical CSR again.  The sort is a least-significant-digit radix sort on 8-bit digits of the
+// column index, written for 64-lane waves:
+//
+//   tiles      a part is cut into tiles of 2048 consecutive entries, one wave per tile
+//   histogram  per tile and digit value; lanes of a wave that hold the same digit find each other
+//              with one ballot per digit bit, and the lowest of them adds their number
+//   scan       one exclusive prefix sum over all counts in (part, digit value, tile) order: the
+//              position where a tile's entries with that digit start.  Parts never mix, because a
+//              part's counts add up to its size
+//   scatter    the wave goes through its tile 64 entries at a time, in order; an entry lands at
+//              start[digit] + (entries with the same digit in lanes below), and the lowest lane
+//              of a digit moves start[digit] on
+//
+// Integer work with unique results: outputs are bit-exact regardless of scheduling.
 #include <cstring>
-
-#include <rocprim/device/device_radix_sort.hpp>
 
 #include "pipad_internal.h"
 
 namespace pipad {
 namespace {
+
+#ifndef PIPAD_SORT_DIGIT
+#define PIPAD_SORT_DIGIT 8
+#endif
+constexpr int kDigitBits = PIPAD_SORT_DIGIT;
+constexpr int kDigits = 1 << kDigitBits;
+#ifndef PIPAD_SORT_TILE
+#define PIPAD_SORT_TILE 2048
+#endif
+constexpr int kTile = PIPAD_SORT_TILE;  // entries per wave
+constexpr int kRounds = kTile / kWave;
+
+struct SortArgs {
+  int32_t nparts;                       // 1 + k
+  int32_t n;
+  uint32_t part_off[PIPAD_MAX_K + 2];   // first entry of every part in the concatenated arrays
+  uint32_t tile_off[PIPAD_MAX_K + 2];   // first tile of every part
+  uint32_t anchor_off[PIPAD_MAX_K + 2]; // first row anchor of every part (one per 64 entries, plus one)
+  const int32_t *rowptr[PIPAD_MAX_K + 1];  // source parts
+  const int32_t *col[PIPAD_MAX_K + 1];
+  int32_t *rowptr_out[PIPAD_MAX_K + 1];    // transposed parts
+  int32_t *col_out[PIPAD_MAX_K + 1];
+  const uint32_t *key_in;
+  const int32_t *val_in;
+  uint32_t *key_out;
+  int32_t *val_out;
+  uint32_t *hist;                       // [sum over parts of kDigits * tiles of the part]
+  int32_t shift;                        // digit = (key >> shift) & 255
+  int32_t last;                         // last pass: values go to col_out of their part
+};
+
+// Part that holds position e of a concatenated array with the given part offsets.
+__device__ inline int part_of(const uint32_t *off, int nparts, uint32_t e) {
+  int p = 0;
+  while (p + 1 < nparts && e >= off[p + 1]) ++p;
+  return p;
+}
 
 // Last row i in [lo, hi] with rowptr[i] <= e, given rowptr[lo] <= e < rowptr[hi + 1].
 __device__ inline int32_t row_of_entry(const int32_t *rp, int32_t lo, int32_t hi, int32_t e) {
@@ -18,33 +71,187 @@ __device__ inline int32_t row_of_entry(const int32_t *rp, int32_t lo, int32_t hi
   return lo;
 }
 
-// row[e] = row that holds entry e: one thread per entry, bisection over the row pointers.
-__global__ __launch_bounds__(kBlock) void k_entry_rows(const int32_t *rowptr, int32_t n, int32_t nnz,
-                                                        int32_t *row) {
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (e >= nnz) return;
-  row[e] = row_of_entry(rowptr, 0, n - 1, (int32_t)e);
+// anchor[p's first anchor + w] = row of part p that holds the part's entry 64 w, for every w with
+// 64 w < nnz_p, and one more slot per part that receives n - 1: one lane per (part, row) writes
+// the (usually zero or one) slots whose entry falls into its row, so that the entries' rows can
+// then be found by a search between two anchors instead of over all rows.
+__global__ __launch_bounds__(kBlock) void k_row_anchors(SortArgs g, int32_t *anchor) {
+  const int64_t id = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (id >= (int64_t)g.n * g.nparts) return;
+  const int p = (int)(id / g.n);
+  const int32_t i = (int32_t)(id - (int64_t)p * g.n);
+  const int32_t a = g.rowptr[p][i], b = g.rowptr[p][i + 1];
+  int32_t *mine = anchor + g.anchor_off[p];
+  for (int64_t w = ((int64_t)a + kWave - 1) / kWave; w * kWave < b; ++w) mine[w] = i;
+  if (i == g.n - 1) mine[((int64_t)b + kWave - 1) / kWave] = g.n - 1;
 }
 
-// Row pointers of a CSR whose entries' row ids are given in ascending order:
-// rowptr[i] = number of ids below i, for i in [0, n].
-__global__ __launch_bounds__(kBlock) void k_rowptr_of_sorted(const uint32_t *ids, int32_t nnz,
-                                                              int32_t n, int32_t *rowptr) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i > n) return;
-  int32_t lo = 0, hi = nnz;
-  while (lo < hi) {
-    const int32_t mid = lo + ((hi - lo) >> 1);
-    if (ids[mid] < (uint32_t)i) lo = mid + 1; else hi = mid;
+// Concatenates the parts: key = column of the entry, value = its row.  One lane per entry of a
+// part, 64 consecutive entries per wave (the grid is cut per part: blockIdx.y), so the rows of a
+// wave's entries lie between two neighbouring anchors.
+__global__ __launch_bounds__(kBlock) void k_sort_input(SortArgs g, const int32_t *anchor,
+                                                        uint32_t *key, int32_t *val) {
+  const int p = blockIdx.y;
+  const int64_t local64 = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int32_t nnz = (int32_t)(g.part_off[p + 1] - g.part_off[p]);
+  if (local64 >= nnz) return;
+  const int32_t local = (int32_t)local64;
+  const int32_t *mine = anchor + g.anchor_off[p];
+  const int32_t w = local / kWave;
+  const int32_t r_lo = min(max(mine[w], 0), g.n - 1);
+  const int32_t r_hi = min(max(mine[w + 1], r_lo), g.n - 1);
+  const uint32_t e = g.part_off[p] + (uint32_t)local;
+  key[e] = (uint32_t)g.col[p][local];
+  val[e] = row_of_entry(g.rowptr[p], r_lo, r_hi, local);
+}
+
+// The lanes of the wave whose digit equals this lane's (bit set = same digit), lanes with
+// `live` false excluded: one ballot per digit bit.
+__device__ inline uint64_t same_digit(uint32_t digit, bool live) {
+  uint64_t mask = __ballot(live);
+#pragma unroll
+  for (int b = 0; b < kDigitBits; ++b) {
+    const bool bit = (digit >> b) & 1u;
+    const uint64_t bal = __ballot(bit);
+    mask &= bit ? bal : ~bal;
   }
-  rowptr[i] = lo;
+  return mask;
 }
 
-// w[e] = dinv_t[col[e]] for one part and one snapshot.
-__global__ __launch_bounds__(kBlock) void k_entry_scales(const int32_t *col, int32_t nnz,
-                                                          const float *dinv_t, float *w) {
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (e < nnz) w[e] = dinv_t[col[e]];
+struct TileRange {
+  int p;
+  uint32_t tile, tiles, begin, end;  // tile number within the part, tiles of the part, entries
+};
+
+__device__ inline TileRange tile_range(const SortArgs &g, uint32_t t) {
+  TileRange r;
+  r.p = part_of(g.tile_off, g.nparts, t);
+  r.tile = t - g.tile_off[r.p];
+  r.tiles = g.tile_off[r.p + 1] - g.tile_off[r.p];
+  r.begin = g.part_off[r.p] + r.tile * (uint32_t)kTile;
+  r.end = min(r.begin + (uint32_t)kTile, g.part_off[r.p + 1]);
+  return r;
+}
+
+// hist[(first count of the part) + digit * tiles + tile] = entries of the tile with that digit.
+__global__ __launch_bounds__(kBlock) void k_radix_hist(SortArgs g) {
+  __shared__ uint32_t cnt[kWavesPerBlock][kDigits];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const uint32_t t = blockIdx.x * kWavesPerBlock + wave;
+  if (t >= g.tile_off[g.nparts]) return;
+  const TileRange r = tile_range(g, t);
+  for (int d = lane; d < kDigits; d += kWave) cnt[wave][d] = 0;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  // the whole tile is requested up front (kRounds loads in flight per lane)
+  uint32_t keys[kRounds];
+#pragma unroll
+  for (int q = 0; q < kRounds; ++q) {
+    const uint32_t e = r.begin + q * kWave + lane;
+    keys[q] = e < r.end ? g.key_in[e] : 0u;
+  }
+#pragma unroll
+  for (int q = 0; q < kRounds; ++q) {
+    const uint32_t e = r.begin + q * kWave + lane;
+    const bool live = e < r.end;
+    const uint32_t digit = (keys[q] >> g.shift) & (kDigits - 1);
+    const uint64_t mask = same_digit(digit, live);
+    if (live && (mask & ((1ull << lane) - 1ull)) == 0) cnt[wave][digit] += (uint32_t)__popcll(mask);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  }
+  const uint64_t hbase = (uint64_t)kDigits * g.tile_off[r.p];
+  for (int d = lane; d < kDigits; d += kWave) g.hist[hbase + (uint64_t)d * r.tiles + r.tile] = cnt[wave][d];
+}
+
+// Stable scatter of one tile by the current digit, from the scanned counts.
+__global__ __launch_bounds__(kBlock) void k_radix_scatter(SortArgs g) {
+  __shared__ uint32_t start[kWavesPerBlock][kDigits];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const uint32_t t = blockIdx.x * kWavesPerBlock + wave;
+  if (t >= g.tile_off[g.nparts]) return;
+  const TileRange r = tile_range(g, t);
+  const uint64_t hbase = (uint64_t)kDigits * g.tile_off[r.p];
+  for (int d = lane; d < kDigits; d += kWave) start[wave][d] = g.hist[hbase + (uint64_t)d * r.tiles + r.tile];
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  int32_t *const dst_col = g.col_out[r.p];
+  const uint32_t part_begin = g.part_off[r.p];
+  // the tile in two halves, each requested up front (kRounds loads in flight per lane)
+  for (int half = 0; half < 2; ++half) {
+    uint32_t keys[kRounds / 2];
+    int32_t vals[kRounds / 2];
+#pragma unroll
+    for (int q = 0; q < kRounds / 2; ++q) {
+      const uint32_t e = r.begin + (half * (kRounds / 2) + q) * kWave + lane;
+      keys[q] = e < r.end ? g.key_in[e] : 0u;
+      vals[q] = e < r.end ? g.val_in[e] : 0;
+    }
+#pragma unroll
+    for (int q = 0; q < kRounds / 2; ++q) {
+      const uint32_t e = r.begin + (half * (kRounds / 2) + q) * kWave + lane;
+      const bool live = e < r.end;
+      const uint32_t key = keys[q];
+      const int32_t val = vals[q];
+      const uint32_t digit = (key >> g.shift) & (kDigits - 1);
+      const uint64_t mask = same_digit(digit, live);
+      const uint64_t below = mask & ((1ull << lane) - 1ull);
+      uint32_t pos = 0;
+      if (live) pos = start[wave][digit] + (uint32_t)__popcll(below);
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // all reads of start before it moves on
+      if (live && below == 0) start[wave][digit] += (uint32_t)__popcll(mask);
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      if (live) {
+        if (g.last) {
+          dst_col[pos - part_begin] = val;  // the transposed part's column indices: the old rows
+          g.key_out[pos] = key;             // (the sorted old columns still give the row pointers)
+        } else {
+          g.key_out[pos] = key;
+          g.val_out[pos] = val;
+        }
+      }
+    }
+  }
+}
+
+// Row pointers of every transposed part from its sorted keys: rowptr[p][i] = keys of part p
+// below i.  One lane per (part, i), i in [0, n].
+__global__ __launch_bounds__(kBlock) void k_rowptr_of_sorted(SortArgs g, const uint32_t *keys) {
+  const int64_t id = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t per = (int64_t)g.n + 1;
+  if (id >= per * g.nparts) return;
+  const int p = (int)(id / per);
+  const uint32_t i = (uint32_t)(id - p * per);
+  uint32_t lo = g.part_off[p], hi = g.part_off[p + 1];
+  while (lo < hi) {
+    const uint32_t mid = lo + ((hi - lo) >> 1);
+    if (keys[mid] < i) lo = mid + 1; else hi = mid;
+  }
+  g.rowptr_out[p][i] = (int32_t)(lo - g.part_off[p]);
+}
+
+// Column scales of the transposed parts' entries: wc[t][e] = dinv_t[col_c[e]] for the overlap
+// part (a node's k scales from the node-major copy of D^-1/2), wd[t][e] = dinv_t[col_d_t[e]] for
+// the exclusive part of snapshot t.  One lane per entry of the concatenated parts.
+struct ScaleArgs {
+  int32_t nparts, n, k;
+  uint32_t part_off[PIPAD_MAX_K + 2];
+  const int32_t *col[PIPAD_MAX_K + 1];
+  const float *dinv, *dinv_nk;
+  float *wc[PIPAD_MAX_K];
+  float *wd[PIPAD_MAX_K];
+};
+
+__global__ __launch_bounds__(kBlock) void k_part_scales(ScaleArgs g) {
+  const int64_t e64 = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e64 >= g.part_off[g.nparts]) return;
+  const uint32_t e = (uint32_t)e64;
+  const int p = part_of(g.part_off, g.nparts, e);
+  const uint32_t local = e - g.part_off[p];
+  const int32_t c = g.col[p][local];
+  if (p == 0) {
+    const float *row = g.dinv_nk + (int64_t)c * g.k;
+    for (int t = 0; t < g.k; ++t) g.wc[t][local] = row[t];
+  } else {
+    g.wd[p - 1][local] = g.dinv[(int64_t)(p - 1) * g.n + c];
+  }
 }
 
 __global__ void k_class_totals(int32_t n, int32_t k, const uint32_t *hubidx, const uint32_t *segoff,
@@ -62,11 +269,7 @@ __global__ void k_class_totals(int32_t n, int32_t k, const uint32_t *hubidx, con
 }  // namespace
 
 // The frame of the transposed patterns with the SAME D^-1/2: aggregating with it multiplies by
-// the transposed normalised adjacency.  Every part is transposed on its own (the transpose of an
-// intersection is the intersection of the transposes): entries are tagged with their row, sorted
-// by column with a stable radix sort (a library primitive, rocPRIM) - rows arrive in ascending
-// order, so they leave in ascending order within every column - and the new row pointers are read
-// off the sorted columns.
+// the transposed normalised adjacency.
 int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx, hipStream_t st,
                     pipad_frame **out) {
   const int32_t n = f->n, k = f->k;
@@ -122,25 +325,44 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
     return PIPAD_OK;
   }
 
-  int32_t max_nnz = g->nnz_c;
-  for (int t = 0; t < k; ++t) max_nnz = std::max(max_nnz, g->nnz_d[t]);
-  int bits = 1;
-  while (((int64_t)1 << bits) < n) ++bits;
-  size_t sort_bytes = 0;
-  if (max_nnz > 0)
-    PIPAD_TRY_T(rocprim::radix_sort_pairs(nullptr, sort_bytes, (const uint32_t *)nullptr,
-                                          (uint32_t *)nullptr, (const int32_t *)nullptr,
-                                          (int32_t *)nullptr, (size_t)max_nnz, 0, bits, st));
+  // ---- the parts side by side, cut into tiles
+  SortArgs s;
+  std::memset(&s, 0, sizeof(s));
+  s.nparts = k + 1;
+  s.n = n;
+  int64_t total = 0, tiles = 0, anchors = 0;
+  int32_t max_nnz = 0;
+  for (int p = 0; p <= k; ++p) {
+    const int32_t nnz = p == 0 ? f->nnz_c : f->nnz_d[p - 1];
+    s.part_off[p] = (uint32_t)total;
+    s.tile_off[p] = (uint32_t)tiles;
+    s.anchor_off[p] = (uint32_t)anchors;
+    total += nnz;
+    tiles += (nnz + kTile - 1) / kTile;
+    anchors += (nnz + kWave - 1) / kWave + 2;
+    max_nnz = std::max(max_nnz, nnz);
+    s.rowptr[p] = p == 0 ? f->rowptr_c : f->rowptr_d[p - 1];
+    s.col[p] = p == 0 ? f->col_c : f->col_d[p - 1];
+    s.rowptr_out[p] = p == 0 ? g->rowptr_c : g->rowptr_d[p - 1];
+    s.col_out[p] = p == 0 ? g->col_c : g->col_d[p - 1];
+  }
+  s.part_off[k + 1] = (uint32_t)total;
+  s.tile_off[k + 1] = (uint32_t)tiles;
+  const int64_t hist_len = std::max<int64_t>(tiles * kDigits, 1);
+  if (total >= ((int64_t)1 << 31) || hist_len >= ((int64_t)1 << 31)) return fail(PIPAD_ERR_TOO_LARGE);
+
   const uint32_t scan_len = (uint32_t)n + 1;
   Arena tmp;
-  int32_t *rows = nullptr;
-  uint32_t *sorted = nullptr, *bsum = nullptr, *shortidx = nullptr, *hubidx = nullptr,
-           *segoff = nullptr, *totals = nullptr, *split_total = nullptr;
-  char *sort_tmp = nullptr;
-  tmp.want(&rows, (size_t)max_nnz);
-  tmp.want(&sorted, (size_t)max_nnz);
-  tmp.want(&sort_tmp, sort_bytes);
-  tmp.want(&bsum, 3 * scan_block_words(scan_len) + 1);
+  uint32_t *key_a = nullptr, *key_b = nullptr, *hist = nullptr, *bsum = nullptr, *shortidx = nullptr,
+           *hubidx = nullptr, *segoff = nullptr, *totals = nullptr, *split_total = nullptr;
+  int32_t *val_a = nullptr, *val_b = nullptr, *anchor = nullptr;
+  tmp.want(&anchor, (size_t)anchors);
+  tmp.want(&key_a, (size_t)total);
+  tmp.want(&key_b, (size_t)total);
+  tmp.want(&val_a, (size_t)total);
+  tmp.want(&val_b, (size_t)total);
+  tmp.want(&hist, (size_t)hist_len);
+  tmp.want(&bsum, std::max(scan_block_words((uint32_t)hist_len), 3 * scan_block_words(scan_len)) + 1);
   tmp.want(&shortidx, (size_t)scan_len);
   tmp.want(&hubidx, (size_t)scan_len);
   tmp.want(&segoff, (size_t)scan_len);
@@ -161,30 +383,58 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
                              hipMemcpyDeviceToDevice, st));
   PIPAD_TRY_T(hipMemcpyAsync(g->dinv_nk, f->dinv_nk, sizeof(float) * (size_t)k * n,
                              hipMemcpyDeviceToDevice, st));
-  for (int part = 0; part <= k; ++part) {
-    const int32_t nnz = part == 0 ? f->nnz_c : f->nnz_d[part - 1];
-    const int32_t *rp = part == 0 ? f->rowptr_c : f->rowptr_d[part - 1];
-    const int32_t *col = part == 0 ? f->col_c : f->col_d[part - 1];
-    int32_t *rp_out = part == 0 ? g->rowptr_c : g->rowptr_d[part - 1];
-    int32_t *col_out = part == 0 ? g->col_c : g->col_d[part - 1];
-    if (nnz > 0) {
-      hipLaunchKernelGGL(k_entry_rows, grid1(nnz, kBlock), dim3(kBlock), 0, st, rp, n, nnz, rows);
-      PIPAD_TRY_T(hipGetLastError());
-      size_t bytes = sort_bytes;
-      PIPAD_TRY_T(rocprim::radix_sort_pairs(sort_tmp, bytes, reinterpret_cast<const uint32_t *>(col),
-                                            sorted, rows, col_out, (size_t)nnz, 0, bits, st));
-    }
-    hipLaunchKernelGGL(k_rowptr_of_sorted, grid1((int64_t)n + 1, kBlock), dim3(kBlock), 0, st, sorted,
-                       nnz, n, rp_out);
-    for (int t = 0; t < k && nnz > 0; ++t) {
-      if (part != 0 && t != part - 1) continue;  // an exclusive part carries its own snapshot's scales
-      float *w = part == 0 ? g->wc[t] : g->wd[t];
-      hipLaunchKernelGGL(k_entry_scales, grid1(nnz, kBlock), dim3(kBlock), 0, st, col_out, nnz,
-                         g->dinv + (size_t)t * n, w);
-    }
-    PIPAD_TRY_T(hipGetLastError());
-  }
 
+  // ---- stable sort of all entries by column, digit by digit
+  const uint32_t *sorted_keys = key_a;
+  if (total > 0) {
+    hipLaunchKernelGGL(k_row_anchors, grid1((int64_t)n * (k + 1), kBlock), dim3(kBlock), 0, st, s, anchor);
+    hipLaunchKernelGGL(k_sort_input, grid1(max_nnz, kBlock, k + 1), dim3(kBlock), 0, st, s, anchor,
+                       key_a, val_a);
+    PIPAD_TRY_T(hipGetLastError());
+    int bits = 1;
+    while (((int64_t)1 << bits) < n) ++bits;
+    const int passes = (bits + kDigitBits - 1) / kDigitBits;
+    s.hist = hist;
+    for (int pass = 0; pass < passes; ++pass) {
+      s.key_in = pass % 2 == 0 ? key_a : key_b;
+      s.val_in = pass % 2 == 0 ? val_a : val_b;
+      s.key_out = pass % 2 == 0 ? key_b : key_a;
+      s.val_out = pass % 2 == 0 ? val_b : val_a;
+      s.shift = pass * kDigitBits;
+      s.last = pass == passes - 1;
+      hipLaunchKernelGGL(k_radix_hist, grid1(tiles, kWavesPerBlock), dim3(kBlock), 0, st, s);
+      PIPAD_TRY_T(hipGetLastError());
+      {
+        uint32_t *one = hist;
+        const int rc = scan_exclusive(&one, 1, (uint32_t)hist_len, bsum, st);
+        if (rc != 0) return fail(rc);
+      }
+      hipLaunchKernelGGL(k_radix_scatter, grid1(tiles, kWavesPerBlock), dim3(kBlock), 0, st, s);
+      PIPAD_TRY_T(hipGetLastError());
+      sorted_keys = s.key_out;
+    }
+  }
+  hipLaunchKernelGGL(k_rowptr_of_sorted, grid1(((int64_t)n + 1) * (k + 1), kBlock), dim3(kBlock), 0, st,
+                     s, sorted_keys);
+  if (total > 0) {
+    ScaleArgs c;
+    std::memset(&c, 0, sizeof(c));
+    c.nparts = k + 1;
+    c.n = n;
+    c.k = k;
+    for (int p = 0; p <= k + 1; ++p) c.part_off[p] = s.part_off[p];
+    for (int p = 0; p <= k; ++p) c.col[p] = s.col_out[p];
+    c.dinv = g->dinv;
+    c.dinv_nk = g->dinv_nk;
+    for (int t = 0; t < k; ++t) {
+      c.wc[t] = g->wc[t];
+      c.wd[t] = g->wd[t];
+    }
+    hipLaunchKernelGGL(k_part_scales, grid1(total, kBlock), dim3(kBlock), 0, st, c);
+  }
+  PIPAD_TRY_T(hipGetLastError());
+
+  // ---- row classes, work lists and the class-grouped copies, as in the build
   {
     const int rc = launch_classify(g, shortidx, hubidx, segoff, split_total, st);
     if (rc != 0) return fail(rc);
