@@ -245,12 +245,19 @@ const char *pipad_last_hip_error(void);
  * Unknown keys, negative values and values beyond a key's range return PIPAD_ERR_INVALID_ARG.
  * Keys (row lengths count common + longest exclusive entries of a row; at most 2^30):
  *   "short_max"      rows with at most this many entries are walked whole by one small lane team,
- *                    several rows per wave (default 32)
- *   "mid_max"        longer rows are split by column class (8 partial sums per row, each walked
- *                    on the XCD that caches its class); up to this length a lane team walks a
- *                    class part, beyond it a whole wave (default 256; below short_max: as short_max)
- *   "hub_threshold"  rows with more entries than this are first cut into units (default 8192)
- *   "hub_segment"    entries per unit of a cut row (default 8192)
+ *                    several rows per wave (default 64)
+ *   "mid_max"        rows up to this length are walked whole by one wave; longer rows ("hub rows")
+ *                    are stored a second time with their entries grouped by a hash class of the
+ *                    column, and the part of a row in class x is walked on XCD x only, whose L2
+ *                    then caches just that class's rows of X; the 8 partial sums per row are added
+ *                    up in a fixed order by a second kernel (default 512; below short_max: as
+ *                    short_max)
+ *   "hub_threshold"  hub rows with more entries than this are first cut into units (default 2048)
+ *   "hub_segment"    entries per unit of a cut row (default 2048)
+ *   "sub_classes"    column classes per XCD, 1, 2 or 4 (other values are rounded down to these):
+ *                    with more than one, the hub rows are walked in that many passes per
+ *                    snapshot, each pass over a smaller share of X (default 1: on MI355X the passes
+ *                    read less from memory but take longer)
  *   "agg_nt"         bit 0: non-temporal stores for Y; bit 1: non-temporal loads for the index and
  *                    scale streams (default 0)
  *   "slice_cols"     feature columns per slice, 1..64 (default 0 = 64)
