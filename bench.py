@@ -33,6 +33,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E peak
+CALIBRATION_BYTES = 1 << 30  # what --calibrate-counters copies (k_stream_copy)
 
 
 def kernel_sources_sha() -> str:
@@ -99,12 +100,17 @@ def write_traffic_profile(workload: str, dirs, bench_line: dict) -> None:
         return m.group(1) if m else n[:40]
 
     kt, pf, pw, pl = dirs
+    fo = bench_line["config"].get("fused_update_cols", 0)
     args = f"--workload {workload} --steps {bench_line['steps']} --warmup {bench_line['warmup']} --no-cpu"
+    if fo:
+        args += f" --update {fo}"
+    tag = f"{workload}_update" if fo else workload
+    agg_kernels = ("k_aggregate_update", "k_split_finish") if fo else ("k_aggregate", "k_split_finish")
     head = (f"# bench.py, workload {workload} (N={bench_line['config']['n']}, k={bench_line['config']['k']}, "
             f"F={bench_line['config']['F']}), one MI355X, kernel sources {kernel_sources_sha()}\n")
     rows = list(csv.DictReader(open(find(kt, "bench_kernel_stats.csv"))))
     out = [head.rstrip(),
-           f"# command: cd /tmp && export TMPDIR=/tmp && rocprofv3 --kernel-trace --stats -d <out> -o bench "
+           f"# command (from the repository root): export TMPDIR=/tmp && rocprofv3 --kernel-trace --stats -d <out> -o bench "
            f"--output-format csv -- python3 bench.py {args}",
            f"# bench.py in the same run: ms_per_step {bench_line['ms_per_step']:.3f}, aggregate_ms (HIP events) "
            f"{bench_line['aggregate_ms']:.3f}, build_overlap_ms {bench_line['build_overlap_ms']:.3f}", "",
@@ -116,17 +122,17 @@ def write_traffic_profile(workload: str, dirs, bench_line: dict) -> None:
             continue
         out.append(f"{n:28s} {r['Calls']:>6s} {float(r['AverageNs'])/1e3:10.1f} {float(r['MinNs'])/1e3:10.1f} "
                    f"{float(r['MaxNs'])/1e3:10.1f} {float(r['TotalDurationNs'])/1e6:10.2f} {float(r['Percentage']):6.2f}")
-        if n in ("k_aggregate", "k_split_finish"):
+        if n in agg_kernels:
             agg_us += float(r["AverageNs"]) / 1e3
-    out += ["", f"k_aggregate + k_split_finish average per call: {agg_us/1e3:.3f} ms  (HIP-event bracket of "
+    out += ["", f"{agg_kernels[0]} + k_split_finish average per call: {agg_us/1e3:.3f} ms  (HIP-event bracket of "
                 f"pipad_frame_aggregate in the same run: {bench_line['aggregate_ms']:.3f} ms)"]
-    open(os.path.join(ROOT, "profiles", f"bench_{workload}_kernel_trace.txt"), "w").write("\n".join(out) + "\n")
+    open(os.path.join(ROOT, "profiles", f"bench_{tag}_kernel_trace.txt"), "w").write("\n".join(out) + "\n")
 
-    def mean_counter(d, counter):
+    def mean_counter(d, counter, kernels=agg_kernels):
         tot = {}
         for r in csv.DictReader(open(find(d, "bench_counter_collection.csv"))):
             n = kname(r["Kernel_Name"])
-            if r["Counter_Name"] == counter and n in ("k_aggregate", "k_split_finish"):
+            if r["Counter_Name"] == counter and n in kernels:
                 tot.setdefault(n, []).append(float(r["Counter_Value"]))
         return sum(sum(v) / len(v) for v in tot.values()), max((len(v) for v in tot.values()), default=0)
 
@@ -134,28 +140,37 @@ def write_traffic_profile(workload: str, dirs, bench_line: dict) -> None:
     w, _ = mean_counter(pw, "WRITE_SIZE")
     hit, _ = mean_counter(pl, "TCC_HIT_sum")
     miss, _ = mean_counter(pl, "TCC_MISS_sum")
-    tb = f * 2 * 1024 + w * 1024
+    # the same counters on the copy kernel of known size that --calibrate-counters ran in those runs
+    cal_kib = CALIBRATION_BYTES / 1024
+    cf, ncf = mean_counter(pf, "FETCH_SIZE", ("k_stream_copy",))
+    cw, ncw = mean_counter(pw, "WRITE_SIZE", ("k_stream_copy",))
+    if not ncf or not ncw:
+        raise SystemExit("the counter runs hold no k_stream_copy dispatch: run them with --calibrate-counters")
+    fscale, wscale = cal_kib / cf, cal_kib / cw
+    tb = (f * fscale + w * wscale) * 1024
     algo = bench_line["roofline"]["algorithmic_bytes"]
     t = [head.rstrip(),
          "# Traffic between the L2s and the memory side (the fabric: served by HBM or by the 256 MB memory-side",
-         "# cache) of one pipad_frame_aggregate call = k_aggregate + k_split_finish; rocprofv3 counters, KiB per dispatch.",
-         f"# commands (one run per line): cd /tmp && export TMPDIR=/tmp && rocprofv3 --pmc FETCH_SIZE -d <out> -o bench "
-         f"--output-format csv -- python3 bench.py {args}",
+         f"# cache) of one {'pipad_frame_aggregate_update' if fo else 'pipad_frame_aggregate'} call = {agg_kernels[0]} + "
+         "k_split_finish; rocprofv3 counters, KiB per dispatch.",
+         f"# commands (from the repository root, one run each): export TMPDIR=/tmp && rocprofv3 --pmc FETCH_SIZE -d <out> -o bench "
+         f"--output-format csv -- python3 bench.py {args} --calibrate-counters",
          "#                              ... --pmc WRITE_SIZE ...  |  ... --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum ...",
          "# summary written by: python3 bench.py --profile-summary <kernel-trace dir> <FETCH dir> <WRITE dir> <L2 dir> "
-         f"--workload {workload}",
-         "# calibration (same counters on a plain float4 copy kernel, 2 GiB -> 2 GiB): FETCH_SIZE read 1048587 KiB for",
-         "#   2097152 KiB actually read (it counts each 128-byte read request as 64 bytes) -> scale 2.0; WRITE_SIZE read",
-         "#   2097152 KiB for 2097152 KiB written -> scale 1.0",
+         f"--workload {workload}  (bench line of the kernel-trace run on stdin)",
+         f"# calibration, in the same runs (--calibrate-counters: k_stream_copy, a plain 16-byte-per-lane copy of "
+         f"{cal_kib:.0f} KiB",
+         f"#   to a separate buffer): FETCH_SIZE read {cf:.0f} KiB for the {cal_kib:.0f} KiB it reads -> scale {fscale:.3f};",
+         f"#   WRITE_SIZE read {cw:.0f} KiB for the {cal_kib:.0f} KiB it writes -> scale {wscale:.3f}",
          f"# mean over {nf} dispatches:",
          f"kernel_sources_sha: {kernel_sources_sha()}",
-         f"fetch_size_kib: {f:.0f}", f"write_size_kib: {w:.0f}", "fetch_scale: 2.0", "write_scale: 1.0",
+         f"fetch_size_kib: {f:.0f}", f"write_size_kib: {w:.0f}", f"fetch_scale: {fscale:.4f}", f"write_scale: {wscale:.4f}",
          f"l2_hits_per_call: {hit:.4g}", f"l2_misses_per_call: {miss:.4g}",
          f"l2_hit_rate: {hit / max(hit + miss, 1):.3f}",
          f"# => {tb/1e9:.2f} GB per call between L2 and memory side; algorithmic (minimal) bytes of the call "
          f"{algo/1e9:.2f} GB; ratio {tb/algo:.2f}",
          f"# => at aggregate_ms {bench_line['aggregate_ms']:.3f}: {tb/bench_line['aggregate_ms']/1e6:.0f} GB/s of fabric traffic"]
-    open(traffic_profile_path(workload), "w").write("\n".join(t) + "\n")
+    open(traffic_profile_path(tag), "w").write("\n".join(t) + "\n")
     print("\n".join(out) + "\n\n" + "\n".join(t))
 
 
@@ -190,6 +205,12 @@ def measure_ceilings(pipad, torch, full: bool):
     ms = _timed(torch, lambda: lib.pipad_ceiling_stream_read(src.data_ptr(), src.numel() * 4,
                                                              sink.data_ptr(), st), 10)
     res["stream_read_GBps"] = src.numel() * 4 / ms / 1e6
+    if full:
+        dst = torch.empty(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB
+        ms = _timed(torch, lambda: lib.pipad_ceiling_stream_copy(src.data_ptr(), dst.data_ptr(),
+                                                                 dst.numel() * 4, st), 10)
+        res["stream_copy_GBps"] = 2 * dst.numel() * 4 / ms / 1e6  # read + written
+        del dst
     count = 1 << 24
     gen = torch.Generator(device="cpu").manual_seed(7)
 
@@ -250,6 +271,10 @@ def main() -> int:
                          "profiles/k_aggregate_<workload>_l2_miss_traffic.txt from four rocprofv3 output "
                          "directories (kernel trace, FETCH_SIZE, WRITE_SIZE, TCC hit/miss) of this "
                          "script; the bench line of the kernel-trace run is read from stdin")
+    ap.add_argument("--calibrate-counters", action="store_true",
+                    help="before the timed steps, run the plain copy kernel of include/pipad_ceilings.h "
+                         "three times (1 GiB each): a profiler's traffic counters are scaled by what "
+                         "they read for it")
     ap.add_argument("--sweep", default=None,
                     choices=["overlap", "features", "sliding", "workloads", "smallf", "rows", "labels", "oracle"],
                     help="print one of the sensitivity tables (bench_sweeps.py) instead of the bench line")
@@ -344,6 +369,17 @@ def main() -> int:
         bt = torch.randn(Fo, generator=gen).to(dev)
         Hs = [torch.empty((n, Fo), dtype=torch.float32, device=dev) for _ in range(k)]
     scratch = torch.empty(1 << 28, dtype=torch.float32, device=dev) if args.cold else None
+    if args.calibrate_counters:
+        import ctypes
+        lib = pipad.load_library()
+        a = torch.ones(CALIBRATION_BYTES // 4, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            rc = lib.pipad_ceiling_stream_copy(a.data_ptr(), b.data_ptr(), CALIBRATION_BYTES,
+                                               ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+            assert rc == 0, rc
+        torch.cuda.synchronize()
+        del a, b
     torch.cuda.synchronize()
     log(f"[bench] features and upload in {time.time() - t0:.1f}s")
 

@@ -1,6 +1,6 @@
 /* pipad_ceilings.h - measurement kernels that bound what the aggregation can reach on this GPU.
  *
- * Not part of the aggregation path: two small kernels with the aggregation kernel's access shapes
+ * Not part of the aggregation path: small kernels with the aggregation kernel's access shapes
  * (16 bytes per lane, four row gathers in flight per lane), used by `bench.py --ceilings` and by
  * bench.py's roofline block to state the attainable bound
  *      max( algorithmic bytes / streaming rate ,  gathered bytes / gather rate )
@@ -24,6 +24,11 @@ extern "C" {
  * that the loads cannot be dropped. */
 int pipad_ceiling_stream_read(const float *src, size_t bytes, float *sink, void *stream);
 
+/* Copies `bytes` (a multiple of 16) from `src` to `dst` (both 16-byte aligned, not overlapping),
+ * 16 bytes per lane.  Besides the copy rate it gives the traffic counters of a profiler a kernel
+ * whose memory traffic is known exactly: `bytes` read and `bytes` written. */
+int pipad_ceiling_stream_copy(const float *src, float *dst, size_t bytes, void *stream);
+
 /* Gathers `count` rows of a row-major float table in the aggregation kernel's access shape and
  * sums them (one float4 per lane team and wave goes to `sink`).
  *   table        device, `rows` rows of `row_floats` floats (16, 32 or 64: a lane team of
@@ -41,7 +46,7 @@ int pipad_ceiling_gather(const float *table, int64_t rows, int32_t row_floats, i
                          const int32_t *index, int64_t count, int32_t xcd_classes, float *sink,
                          void *stream);
 
-/* Floats the `sink` argument of both calls must hold. */
+/* Floats the `sink` argument of the calls above must hold. */
 size_t pipad_ceiling_sink_floats(void);
 
 #ifdef __cplusplus

@@ -66,6 +66,7 @@ SIGNATURES = {
     "pipad_set_option": (ctypes.c_int, [ctypes.c_char_p, _i64]),
     # include/pipad_ceilings.h (measurement kernels)
     "pipad_ceiling_stream_read": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, _vp]),
+    "pipad_ceiling_stream_copy": (ctypes.c_int, [_vp, _vp, ctypes.c_size_t, _vp]),
     "pipad_ceiling_gather": (ctypes.c_int, [_vp, _i64, _i32, _i64, _vp, _i64, _i32, _vp, _vp]),
     "pipad_ceiling_sink_floats": (ctypes.c_size_t, []),
     "pipad_get_option": (ctypes.c_int, [ctypes.c_char_p, ctypes.POINTER(_i64)]),

@@ -4,6 +4,10 @@
 #include "pipad_ceilings.h"
 #include "pipad_internal.h"
 
+#ifndef PIPAD_STREAM_BLOCKS
+#define PIPAD_STREAM_BLOCKS 2048  // workgroups of the streaming kernels: eight per CU
+#endif
+
 namespace pipad {
 namespace {
 
@@ -29,6 +33,21 @@ __global__ __launch_bounds__(kBlock) void k_stream_read(const float4 *src, size_
   float s = acc.x + acc.y + acc.z + acc.w;
   for (int m = kWave >> 1; m >= 1; m >>= 1) s += __shfl_xor(s, m, kWave);
   if (threadIdx.x % kWave == 0) sink[(size_t)(blockIdx.x * kWavesPerBlock + threadIdx.x / kWave) % kSinkFloats] = s;
+}
+
+// Plain copy, 16 bytes per lane, four loads in flight: its memory traffic is known exactly (bytes
+// read = bytes written = the argument), which is what hardware traffic counters are scaled by.
+__global__ __launch_bounds__(kBlock) void k_stream_copy(const float4 *src, float4 *dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * kBlock;
+  size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const float4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a;
+    dst[i + stride] = b;
+    dst[i + 2 * stride] = c;
+    dst[i + 3 * stride] = d;
+  }
+  for (; i < n16; i += stride) dst[i] = src[i];
 }
 
 // A wave owns 1024 consecutive index entries; its 64 / LS lane teams take entries team, team +
@@ -85,13 +104,25 @@ int pipad_ceiling_stream_read(const float *src, size_t bytes, float *sink, void 
     return PIPAD_ERR_INVALID_ARG;
   if (bytes == 0) return PIPAD_OK;
   const size_t n16 = bytes / 16;
-#ifndef PIPAD_STREAM_BLOCKS
-#define PIPAD_STREAM_BLOCKS 2048  // eight workgroups per CU
-#endif
   const unsigned blocks =
       (unsigned)std::min<size_t>(PIPAD_STREAM_BLOCKS, (n16 + pipad::kBlock - 1) / pipad::kBlock);
   hipLaunchKernelGGL(pipad::k_stream_read, dim3(blocks), dim3(pipad::kBlock), 0,
                      static_cast<hipStream_t>(stream), reinterpret_cast<const float4 *>(src), n16, sink);
+  PIPAD_HIP(hipGetLastError());
+  return PIPAD_OK;
+}
+
+int pipad_ceiling_stream_copy(const float *src, float *dst, size_t bytes, void *stream) {
+  const uintptr_t a = reinterpret_cast<uintptr_t>(src), b = reinterpret_cast<uintptr_t>(dst);
+  if (!src || !dst || bytes % 16 != 0 || ((a | b) & 15u)) return PIPAD_ERR_INVALID_ARG;
+  if (a < b + bytes && b < a + bytes) return PIPAD_ERR_INVALID_ARG;  // overlapping
+  if (bytes == 0) return PIPAD_OK;
+  const size_t n16 = bytes / 16;
+  const unsigned blocks =
+      (unsigned)std::min<size_t>(PIPAD_STREAM_BLOCKS, (n16 + pipad::kBlock - 1) / pipad::kBlock);
+  hipLaunchKernelGGL(pipad::k_stream_copy, dim3(blocks), dim3(pipad::kBlock), 0,
+                     static_cast<hipStream_t>(stream), reinterpret_cast<const float4 *>(src),
+                     reinterpret_cast<float4 *>(dst), n16);
   PIPAD_HIP(hipGetLastError());
   return PIPAD_OK;
 }
