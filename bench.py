@@ -293,6 +293,10 @@ def main() -> int:
         return 0
     if args.sweep:
         import bench_sweeps
+        import paper_2301_00391_amd as pipad
+        for item in args.opt:  # defaults the sweep's frames are built with (where it sets none itself)
+            key, _, val = item.partition("=")
+            pipad.set_option(key, int(val))
         return bench_sweeps.main(["bench_sweeps", args.sweep])
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "

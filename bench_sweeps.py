@@ -240,21 +240,23 @@ def small_f_sweep(dev):
         snaps = synth.graphs(n, cfg.edges, k, cfg.churn, cfg.model, cfg.params, cfg.seed)
         gs = [(torch.from_numpy(snaps.rowptr[t]).to(dev), torch.from_numpy(snaps.col[t]).to(dev))
               for t in range(k)]
-        frame = pipad.frame_build_overlap(gs)
+        # a frame keeps the options it was built with: one frame per setting of agg_coalescent
+        frames = {}
+        for mode in (2, 0, 1):
+            pipad.set_option("agg_coalescent", mode)
+            frames[mode] = pipad.frame_build_overlap(gs)
         for feat in (2, 6, 16):
             xw = torch.rand((n, k, feat), device=dev) * 2 - 1
             yw = torch.empty_like(xw)
             xl = [xw[:, t, :].contiguous() for t in range(k)]
             yl = [torch.empty_like(x) for x in xl]
-            pipad.set_option("agg_coalescent", 2)
-            t_co = _time(lambda: pipad.frame_aggregate(frame, xw, yw))
-            pipad.set_option("agg_coalescent", 0)
-            t_ws = _time(lambda: pipad.frame_aggregate(frame, xw, yw))
-            t_ls = _time(lambda: pipad.frame_aggregate(frame, xl, yl))
-            pipad.set_option("agg_coalescent", 1)
-            t_auto = _time(lambda: pipad.frame_aggregate(frame, xw, yw))
+            t_co = _time(lambda: pipad.frame_aggregate(frames[2], xw, yw))
+            t_ws = _time(lambda: pipad.frame_aggregate(frames[0], xw, yw))
+            t_ls = _time(lambda: pipad.frame_aggregate(frames[0], xl, yl))
+            t_auto = _time(lambda: pipad.frame_aggregate(frames[1], xw, yw))
             print(f"| {name} | {feat} | {t_co:.3f} | {t_ws:.3f} | {t_ls:.3f} | {t_auto:.3f} |", flush=True)
-        frame.close()
+        for fr in frames.values():
+            fr.close()
 
 
 def row_class_sweep(dev):

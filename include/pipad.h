@@ -106,12 +106,15 @@ int pipad_frame_build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, ui
 int pipad_frame_temporaries(pipad_frame_t *frame, void **ptr, size_t *bytes);
 
 /* Row stride, in floats, that the feature matrices X should have when their rows are gathered
- * by pipad_frame_aggregate: the smallest ODD number of 128-byte lines that holds F floats
- * (F = 64 -> 96, F = 128 -> 160, F <= 32 -> 32).  The call works with any ldx >= F; but with a
- * power-of-two stride the memory channel of a row is decided by a few bits of the node id, and
- * when popular nodes share those bits (ids of R-MAT-like generators do) their rows crowd onto a
- * few channels: measured on a 1M-node R-MAT frame at F = 64, ldx = 64 is 4-8 % slower than
- * ldx = 96.  The padding is never read.  Returns a negative pipad_status for F < 1. */
+ * by pipad_frame_aggregate.  Rows of up to 128 bytes: the smallest power of two >= F, so that no
+ * row straddles two 128-byte lines and nothing more is padded (F = 6 -> 8, F = 16 -> 16,
+ * F = 20 -> 32; padding such rows to a whole line was measured 15-50 % slower).  Longer rows:
+ * the smallest ODD number of 128-byte lines that holds F floats (F = 64 -> 96, F = 128 -> 160).
+ * The call works with any ldx >= F; but with a power-of-two stride of several lines the memory
+ * channel of a row is decided by a few bits of the node id, and when popular nodes share those
+ * bits (ids of R-MAT-like generators do) their rows crowd onto a few channels: measured on a
+ * 1M-node R-MAT frame at F = 64, ldx = 64 is 1-5 % slower than ldx = 96.  The padding is never
+ * read.  Returns a negative pipad_status for F < 1. */
 int64_t pipad_recommended_row_stride(int32_t F);
 
 /* Borrowed views (valid until the frame is destroyed) of the overlap part and of the exclusive
@@ -258,6 +261,12 @@ const char *pipad_last_hip_error(void);
  *                    with more than one, the hub rows are walked in that many passes per
  *                    snapshot, each pass over a smaller share of X (default 1: on MI355X the passes
  *                    read less from memory but take longer)
+ *   "agg_order"      order of the workgroups of one call.  1: the slices (64 columns of one
+ *                    snapshot) one after the other, so that the caches hold one snapshot's
+ *                    matrix at a time; 0: the same rows of all slices side by side, so that the
+ *                    slices share the entry lists they have in common (the overlap part is read
+ *                    once for all snapshots); 2 (default): 0 while one slice's matrix is smaller
+ *                    than 28 MiB, else 1.  Results do not depend on it.
  *   "agg_nt"         bit 0: non-temporal stores for Y; bit 1: non-temporal loads for the index and
  *                    scale streams (default 0)
  *   "slice_cols"     feature columns per slice, 1..64 (default 0 = 64)

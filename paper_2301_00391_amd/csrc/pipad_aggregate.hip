@@ -50,6 +50,9 @@
 
 #include "pipad_internal.h"
 
+#ifndef PIPAD_ORDER_BYTES
+#define PIPAD_ORDER_BYTES (28 << 20)
+#endif
 #ifndef PIPAD_PARTIAL_NT
 #define PIPAD_PARTIAL_NT 0
 #endif
@@ -81,6 +84,7 @@ struct AggArgs {
   int32_t blocks_wide, blocks_mid, blocks_short;
   int32_t batch_short, batch_mid, batch_wide;  // rows / class parts per wave
   int64_t blocks_per_phase;
+  int32_t order;      // 1: one slice after the other; 0: hub class parts so, the rows of all slices side by side
   int32_t sub_log2;   // log2 of the sub classes per XCD
   int32_t nclass;     // 8 << sub_log2
   int64_t nv;         // class parts per part of the frame = nclass * n_units
@@ -438,8 +442,30 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
   // through the slices (snapshot-major) one after the other, and within a slice's class parts the
   // class of a workgroup is its index mod 8.
   const int64_t b = blockIdx.x;
-  const int slice_seq = (int)(b / a.blocks_per_phase);
-  int64_t w = b - slice_seq * a.blocks_per_phase;
+  const int nsub = 1 << a.sub_log2;
+  const int64_t wide_blocks = (int64_t)kClasses * a.blocks_wide;  // per sub class
+  const int64_t split_blocks = nsub * wide_blocks;
+  int slice_seq;
+  int64_t w;  // workgroup index within the slice's phase: class parts, mid rows, short rows
+  if (a.order == 1) {
+    slice_seq = (int)(b / a.blocks_per_phase);
+    w = b - slice_seq * a.blocks_per_phase;
+  } else {
+    // Side by side: neighbouring workgroups take the same rows in different slices, so the
+    // entry lists they share (the overlap part's indices, the row pointers) are fetched once for
+    // all of them - what pays while the operand is small next to the index streams.  The class
+    // parts keep their slice-after-slice order in front (their class is the workgroup index mod 8).
+    const int nsl = a.nsel * a.fchunks;
+    const int64_t hub_total = split_blocks * nsl;
+    if (b < hub_total) {
+      slice_seq = (int)(b / split_blocks);
+      w = b - slice_seq * split_blocks;
+    } else {
+      const int64_t r = b - hub_total;
+      slice_seq = (int)(r % nsl);
+      w = split_blocks + r / nsl;
+    }
+  }
   const int t_seq = slice_seq / a.fchunks;
   const int slice = (slice_seq - t_seq * a.fchunks) * a.k + selected_snapshot(a, t_seq);
   const Slice s = slice_setup(a, slice, fl, VEC);
@@ -454,12 +480,9 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
   //      their way.
   // (every field is read into a local before the control flow that chooses among them, so that
   // the kernel arguments are only ever read at constant offsets)
-  const int nsub = 1 << a.sub_log2;
   const int32_t *const p_items = a.item_row, *const p_mid = a.rows_long, *const p_short = a.rows_short;
   const int64_t n_items = a.n_items, n_mid = a.n_long, n_short = a.n_short;
   const int b_wide = a.batch_wide, b_mid = a.batch_mid, b_short = a.batch_short;
-  const int64_t wide_blocks = (int64_t)kClasses * a.blocks_wide;  // per sub class
-  const int64_t split_blocks = nsub * wide_blocks;
   const bool split = w < split_blocks;                  // class parts of hub units
   const bool wide = w < split_blocks + a.blocks_mid;    // ... or whole mid rows: a wave per list
   int cls = 0;  // column class of this wave's class parts
@@ -1144,6 +1167,11 @@ int aggregate_launch(const pipad_frame *f, int32_t F, const float *const *X, int
   a.n_items = f->n_items;
   a.n_hub = f->n_hub;
   a.nt = (int32_t)opt.agg_nt;
+  // Workgroup order.  One slice after the other keeps one snapshot's matrix in the caches at a
+  // time; side by side shares the index streams between the slices, which wins (8-18 % measured
+  // on N = 200k, F <= 32) while a slice's matrix (N rows of the slice's width) is smaller than
+  // the eight L2s together; from PIPAD_ORDER_BYTES on the slices go one after the other.
+  a.order = opt.agg_order >= 2 ? -1 : (int32_t)opt.agg_order;
   a.nsel = subset ? nsubset : f->k;
   for (int q = 0; q < a.nsel; ++q)
     a.sel[q >> 3] |= (uint64_t)(subset ? subset[q] : q) << ((q & 7) * 8);
@@ -1207,21 +1235,25 @@ int aggregate_launch(const pipad_frame *f, int32_t F, const float *const *X, int
   }
   const int sw = (1 << a.ls_log2) * vec;
   const int nteams = kWave >> a.ls_log2;
+  if (a.order < 0) a.order = (int64_t)f->n * sw * 4 >= (int64_t)PIPAD_ORDER_BYTES ? 1 : 0;
 
-  // Rows per wave: the full batches amortise the per-wave set-up on big frames; a small frame gets
-  // shorter ones (down to one step per wave), until what runs together -- one slice, or all
-  // snapshot groups of the coalescent kernel -- has a few waves for every slot of the chip or the
-  // batches cannot shrink further.
+  // Rows per wave: the full batches amortise the per-wave set-up (and let a wave request its next
+  // row while it gathers the current one) on big frames; a small frame gets shorter ones (down to
+  // one step per wave), until what runs together -- one slice, or all of them when they go side
+  // by side -- has a few waves for every slot of the chip or the batches cannot shrink further.
+  // (Measured on N = 200k .. 500k frames: slices that follow one another lose 5-10 % with full
+  // batches although the launch as a whole has waves enough; side by side gains as much.)
   {
     const int64_t enough = 4 * 8192;  // waves
     a.batch_short = kShortRowsPerWave;
     a.batch_mid = kLongRowsPerWave;
     a.batch_wide = coalescent ? 1 : kWideUnitsPerWave;
     const int min_mid = 1;
-    const int64_t mult = coalescent ? a.nslices : 1;
-    const int64_t mult_wide = coalescent ? a.nslices : f->nclass;
+    const int64_t slices_run = coalescent ? a.nslices : a.order == 0 ? (int64_t)a.nsel * a.fchunks : 1;
+    const int64_t mult = slices_run;
+    const int64_t mult_wide = slices_run * (coalescent ? 1 : f->nclass);
     auto waves = [&]() {
-      return (int64_t)(f->n_short + a.batch_short - 1) / a.batch_short * (coalescent ? a.nslices : 1) +
+      return (int64_t)(f->n_short + a.batch_short - 1) / a.batch_short * slices_run +
              (int64_t)(f->n_long + a.batch_mid - 1) / a.batch_mid * mult +
              (int64_t)(f->n_items + a.batch_wide - 1) / a.batch_wide * mult_wide;
     };

@@ -190,6 +190,11 @@ int pipad_frame_transpose(const pipad_frame_t *frame, pipad_alloc_fn alloc, void
 
 int64_t pipad_recommended_row_stride(int32_t F) {
   if (F < 1) return PIPAD_ERR_INVALID_ARG;
+  if (F <= 32) {  // within one line: the next power of two, so that no row straddles two lines
+    int64_t p = 1;
+    while (p < F) p <<= 1;
+    return p;
+  }
   int64_t lines = ((int64_t)F * 4 + 127) / 128;  // 128-byte lines that hold a row
   if (lines % 2 == 0) ++lines;                    // ... made odd
   return lines * 32;
@@ -229,7 +234,7 @@ static int64_t *option_slot(const char *key, int64_t *max_value) {
   const Slot slots[] = {
       {"short_max", &o.short_max, len_max},     {"mid_max", &o.mid_max, len_max},
       {"hub_threshold", &o.hub_threshold, len_max}, {"hub_segment", &o.hub_segment, len_max},
-      {"sub_classes", &o.sub_classes, 4},
+      {"sub_classes", &o.sub_classes, 4},       {"agg_order", &o.agg_order, 2},
       {"agg_nt", &o.agg_nt, 3},                 {"agg_generic", &o.agg_generic, 1},
       {"slice_cols", &o.slice_cols, 64},        {"agg_coalescent", &o.agg_coalescent, 2},
   };

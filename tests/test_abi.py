@@ -54,10 +54,16 @@ def test_coalescent_row_bytes_match_the_paper(golden_dir):
         assert pipad.coalescent_row_bytes(snaps, feat) == nbytes
 
 
-def test_padded_row_stride_is_an_odd_number_of_128_byte_lines():
+def test_padded_row_stride():
+    """Rows within one 128-byte line: the next power of two (no row straddles two lines); longer
+    rows: an odd number of 128-byte lines."""
     import paper_2301_00391_amd as pipad
-    for feat in (1, 2, 31, 32, 33, 64, 96, 128, 130, 256):
+    for feat in (33, 64, 96, 128, 130, 256):
         stride = pipad.padded_row_stride(feat)
         assert stride >= feat and stride % 32 == 0 and (stride // 32) % 2 == 1
         assert stride - feat < 64  # never more than two lines of padding
+    for feat in range(1, 33):
+        stride = pipad.padded_row_stride(feat)
+        assert feat <= stride < 2 * feat and stride & (stride - 1) == 0
     assert pipad.padded_row_stride(64) == 96 and pipad.padded_row_stride(32) == 32
+    assert pipad.padded_row_stride(6) == 8 and pipad.padded_row_stride(16) == 16

@@ -13,7 +13,7 @@ from _util import check_overlap, check_y, csr_to_coo, to_gpu_snapshots
 pytestmark = pytest.mark.gpu
 
 DEFAULT_OPTIONS = {"short_max": 64, "mid_max": 512, "hub_threshold": 2048, "hub_segment": 2048,
-                   "sub_classes": 1, "agg_nt": 0, "agg_generic": 0, "agg_coalescent": 1, "slice_cols": 0}
+                   "sub_classes": 1, "agg_order": 2, "agg_nt": 0, "agg_generic": 0, "agg_coalescent": 1, "slice_cols": 0}
 
 torch = pytest.importorskip("torch")
 
@@ -89,10 +89,11 @@ def churned(rng, n, k, p, keep, symmetric=True):
     return out
 
 
-@pytest.mark.parametrize("nt,coalescent,mid_max", [(0, 1, 256), (3, 2, 40)])
+@pytest.mark.parametrize("nt,coalescent,mid_max,order", [(0, 1, 256, 2), (3, 2, 40, 1), (0, 0, 10, 0)])
 @pytest.mark.parametrize("layout", ["list", "wide"])
-def test_tiny_config(pipad, nt, coalescent, mid_max, layout):
+def test_tiny_config(pipad, nt, coalescent, mid_max, order, layout):
     pipad.set_option("agg_nt", nt)
+    pipad.set_option("agg_order", order)
     pipad.set_option("agg_coalescent", coalescent)
     pipad.set_option("mid_max", mid_max)
     cfg = synth.CONFIGS["tiny"]
@@ -126,9 +127,10 @@ def test_shapes_and_feature_widths(pipad, k, F, short_max, generic, mid_max):
 @pytest.mark.parametrize("short_max,mid_max,threshold,segment",
                          [(2, 8, 14, 4), (0, 0, 1, 1), (5, 5, 5, 3), (0, 20, 9, 70), (3, 1000, 6, 4)])
 def test_row_classes_short_mid_hub(pipad, short_max, mid_max, threshold, segment, sub_classes):
-    """Low thresholds push rows through all three paths (whole short rows, class parts of mid rows
-    walked by lane teams, class parts of hub units walked by waves); very long rows are cut into
-    units; the partial sums of a row are added in a fixed order."""
+    """Low thresholds push rows through all three paths (whole short rows walked by lane teams,
+    whole mid rows by a wave, class parts of hub rows by a wave each, with one or several
+    classes per XCD); very long rows are cut into units; the partial sums of a row are added in
+    a fixed order."""
     pipad.set_option("short_max", short_max)
     pipad.set_option("mid_max", mid_max)
     pipad.set_option("hub_threshold", threshold)
@@ -147,6 +149,35 @@ def test_row_classes_short_mid_hub(pipad, short_max, mid_max, threshold, segment
     run_case(pipad, n, lists, 16, seed=8, layout="wide")
     run_case(pipad, n, lists, 6, seed=9, layout="wide")
     run_case(pipad, n, lists, 3, seed=10, layout="wide")
+
+
+def test_a_frame_keeps_the_options_it_was_built_with(pipad):
+    """Options are copied into the frame by the build: changing them afterwards must not change a
+    bit of what the frame computes, while a frame built afterwards takes the new values (here: all
+    rows become hub rows cut into small units, which sums in another order)."""
+    rng = np.random.default_rng(99)
+    n, k, F = 600, 3, 64
+    lists = churned(rng, n, k, 0.05, 0.8)
+    dev = "cuda:0"
+    snaps = [(torch.from_numpy(rp).to(dev), torch.from_numpy(c).to(dev)) for rp, c in lists]
+    xs = [torch.from_numpy(synth.features(3, t, n, F)).to(dev) for t in range(k)]
+    frame = pipad.frame_build_overlap(snaps)
+    before = [y.clone() for y in pipad.frame_aggregate(frame, xs)]
+    for key, val in (("short_max", 0), ("mid_max", 0), ("hub_threshold", 4), ("hub_segment", 4),
+                     ("sub_classes", 4), ("agg_generic", 1)):
+        pipad.set_option(key, val)
+    after = pipad.frame_aggregate(frame, xs)
+    other = pipad.frame_build_overlap(snaps)
+    different = pipad.frame_aggregate(other, xs)
+    torch.cuda.synchronize()
+    for t in range(k):
+        assert torch.equal(before[t], after[t]), f"snapshot {t}"
+    assert any(not torch.equal(before[t], different[t]) for t in range(k)), \
+        "the new options did not reach the frame built after them"
+    for t in range(k):
+        assert torch.allclose(before[t], different[t], rtol=1e-4, atol=1e-5)
+    frame.close()
+    other.close()
 
 
 @pytest.mark.parametrize("k,F", [(8, 2), (8, 6), (4, 16), (8, 16), (2, 30), (32, 2), (3, 5)])
