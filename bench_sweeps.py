@@ -306,7 +306,12 @@ def label_sweep(dev):
     rng = np.random.default_rng(0)
     perms = {"natural ids (R-MAT: popularity tied to the id's bits)": None,
              "random ids": rng.permutation(n).astype(np.int64),
-             "ids sorted by degree (hubs first)": np.argsort(np.argsort(-deg, kind="stable"), kind="stable")}
+             "ids sorted by degree (hubs first)": np.argsort(np.argsort(-deg, kind="stable"), kind="stable"),
+             # neighbours in memory stay neighbours; only the order inside every 256 ids changes
+             "ids sorted by degree within aligned blocks of 256":
+                 np.argsort(np.lexsort((-deg, np.arange(n) // 256)), kind="stable"),
+             "ids sorted by degree within aligned blocks of 4096":
+                 np.argsort(np.lexsort((-deg, np.arange(n) // 4096)), kind="stable")}
     stride = pipad.padded_row_stride(feat)
     print("large frame (N = 1M R-MAT, k = 8, F = 64), aggregation ms per call\n")
     print("| node labels | rows of X padded (stride 96 floats) | rows of X dense (stride 64) |")
