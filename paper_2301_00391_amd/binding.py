@@ -174,7 +174,11 @@ class Frame:
             load_library().pipad_frame_destroy(self._h)
             self._h = None
             self._temp = None
-            self._buffers = []
+            # in place: the allocator callback's closure holds the same list, and ctypes callback
+            # objects sit in a reference cycle that only the garbage collector breaks - rebinding
+            # the attribute would keep every buffer alive until its next run
+            self._buffers.clear()
+            self._callback = None
 
     def __del__(self):
         try:

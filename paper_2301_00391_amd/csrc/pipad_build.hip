@@ -748,13 +748,28 @@ __global__ __launch_bounds__(kBlock) void k_scatter_delta(Snaps s, Parts p, cons
   uint32_t dst = pre[off + w] - pre[off];
   const int32_t *col = s.col[t] + (int64_t)w * 64;
   const float *dinv_t = dinv + (int64_t)t * n;
+  // four entries per round: their column loads, then their scale gathers, are in flight together
+  constexpr int R = 4;
   while (sel) {
-    const int bit = __ffsll((unsigned long long)sel) - 1;
-    sel &= sel - 1;
-    const int32_t c = col[bit];
-    p.col_out[part][dst] = c;
-    p.wd[t][dst] = dinv_t[c];
-    ++dst;
+    int32_t c[R];
+    float d[R];
+    bool have[R];
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+      have[u] = sel != 0;
+      const int bit = have[u] ? __ffsll((unsigned long long)sel) - 1 : 0;
+      sel &= sel - 1;  // (stays 0)
+      c[u] = have[u] ? col[bit] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < R; ++u) d[u] = have[u] ? dinv_t[c[u]] : 0.f;
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+      if (have[u]) {
+        p.col_out[part][dst] = c[u];
+        p.wd[t][dst] = d[u];
+        ++dst;
+      }
   }
 }
 
@@ -799,6 +814,22 @@ int scan_exclusive(uint32_t *const *data, int count, uint32_t m, uint32_t *bsum,
 }
 
 size_t scan_block_words(uint32_t m) { return ((size_t)m + kScanTile - 1) / kScanTile; }
+
+// A few pinned host words per thread for the sizes a build reads back (allocated at the thread's
+// first build, kept until the process ends); null when pinned memory cannot be had.
+static uint32_t *pinned_words() {
+  thread_local uint32_t *buf = nullptr;
+  thread_local bool tried = false;
+  if (!tried) {
+    tried = true;
+    void *ptr = nullptr;
+    if (hipHostMalloc(&ptr, sizeof(uint32_t) * (2 * PIPAD_MAX_K + 8), hipHostMallocPortable) == hipSuccess)
+      buf = static_cast<uint32_t *>(ptr);
+    else
+      (void)hipGetLastError();
+  }
+  return buf;
+}
 
 void frame_take_options(pipad_frame *f) {
   const int64_t lim = (int64_t)1 << 30;  // thresholds beyond any int32 row length mean "never"
@@ -1056,8 +1087,6 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   }
   hipLaunchKernelGGL(k_rowptr, grid1((int64_t)n + 1, kBlock, k + 1), dim3(kBlock), 0, st, s, p,
                      pre, n);
-  if (n > 0)
-    hipLaunchKernelGGL(k_dinv, grid1(n, kBlock), dim3(kBlock), 0, st, s, n, k, f->dinv, f->dinv_nk);
   PIPAD_TRY(hipGetLastError());
   {
     const int rc = launch_classify(f, shortidx, hubidx, segoff, split_total, st);
@@ -1069,14 +1098,36 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     if (rc != 0) return fail(rc);
   }
 
-  // ---- the one host synchronisation: sizes of the data-dependent outputs
-  uint32_t host_totals[2 * PIPAD_MAX_K + 8];
+  // ---- the one host synchronisation: sizes of the data-dependent outputs.  The host waits for
+  // an event behind the copy, and D^-1/2 - which nothing before this point needs - is computed
+  // behind that event, while the host sizes and requests the output buffers.
+  uint32_t stack_totals[2 * PIPAD_MAX_K + 8];
+  uint32_t *host_totals = pinned_words();
   hipLaunchKernelGGL(k_totals, dim3(1), dim3(kWave), 0, st, p, pre, k, n, hubidx, segoff, shortidx,
                      split_total, totals);
   PIPAD_TRY(hipGetLastError());
+  hipEvent_t copied = nullptr;
+  if (host_totals && hipEventCreateWithFlags(&copied, hipEventDisableTiming) != hipSuccess) {
+    (void)hipGetLastError();
+    copied = nullptr;
+  }
+  if (!copied) host_totals = stack_totals;
   PIPAD_TRY(hipMemcpyAsync(host_totals, totals, sizeof(uint32_t) * (size_t)(2 * k + 6),
                            hipMemcpyDeviceToHost, st));
-  PIPAD_TRY(hipStreamSynchronize(st));
+  if (copied) {
+    hipError_t e = hipEventRecord(copied, st);
+    if (e == hipSuccess && n > 0)
+      hipLaunchKernelGGL(k_dinv, grid1(n, kBlock), dim3(kBlock), 0, st, s, n, k, f->dinv, f->dinv_nk);
+    if (e == hipSuccess) e = hipEventSynchronize(copied);
+    (void)hipEventDestroy(copied);
+    PIPAD_TRY(e);
+    PIPAD_TRY(hipGetLastError());
+  } else {
+    PIPAD_TRY(hipStreamSynchronize(st));
+    if (n > 0)
+      hipLaunchKernelGGL(k_dinv, grid1(n, kBlock), dim3(kBlock), 0, st, s, n, k, f->dinv, f->dinv_nk);
+    PIPAD_TRY(hipGetLastError());
+  }
 
   f->nnz_c = (int32_t)(host_totals[1] - host_totals[0]);
   for (int t = 0; t < k; ++t) f->nnz_d[t] = (int32_t)(host_totals[2 + t] - host_totals[1 + t]);
