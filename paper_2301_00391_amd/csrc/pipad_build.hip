@@ -734,42 +734,61 @@ __global__ __launch_bounds__(kBlock) void k_scatter_common(Snaps s, Parts p, con
   }
 }
 
-// Exclusive parts (grid.y = snapshot): usually few entries are selected, so one lane takes a whole
-// 64-entry word and walks its set bits.
+// Exclusive parts (grid.y = snapshot): usually few entries are selected.  A wave takes 64
+// consecutive 64-entry words; its selected entries are consecutive in the output, so lane l takes
+// the l-th, l + 64-th, ... of them: it finds the word (a search over the words' running counts)
+// and the bit (the r-th set bit of that word), and the wave's stores are contiguous.
+__device__ inline int nth_set_bit(uint64_t x, int r) {  // position of the r-th (0-based) set bit
+  int pos = 0;
+#pragma unroll
+  for (int width = 32; width >= 1; width >>= 1) {
+    const int c = __popcll(x & (((1ull << width) - 1ull) << pos));
+    if (r >= c) {
+      r -= c;
+      pos += width;
+    }
+  }
+  return pos;
+}
+
 __global__ __launch_bounds__(kBlock) void k_scatter_delta(Snaps s, Parts p, const uint32_t *pre,
                                                            const float *dinv, int32_t n) {
   const int t = blockIdx.y;
   const int part = 1 + t;
+  const int lane = threadIdx.x % kWave;
   const uint32_t nw = p.word_off[part + 1] - p.word_off[part];
-  const uint32_t w = blockIdx.x * kBlock + threadIdx.x;
-  if (w >= nw) return;
-  uint64_t sel = selected_word(p, s, part, w);
+  const uint32_t w0 = (blockIdx.x * kWavesPerBlock + threadIdx.x / kWave) * kWave;  // first word of the wave
+  if (w0 >= nw) return;
+  const uint32_t w = w0 + lane;
+  const uint64_t sel = w < nw ? selected_word(p, s, part, w) : 0ull;
   const uint32_t off = p.word_off[part];
-  uint32_t dst = pre[off + w] - pre[off];
-  const int32_t *col = s.col[t] + (int64_t)w * 64;
+  const uint32_t dst0 = pre[off + w0] - pre[off];
+  int incl = __popcll(sel);  // running count of selected entries up to and including this word
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const int up = __shfl_up(incl, d, kWave);
+    if (lane >= d) incl += up;
+  }
+  const int total = __shfl(incl, kWave - 1, kWave);
+  const int excl = incl - __popcll(sel);
+  const uint32_t sel_lo = (uint32_t)sel, sel_hi = (uint32_t)(sel >> 32);
+  const int32_t *col = s.col[t] + (int64_t)w0 * 64;
   const float *dinv_t = dinv + (int64_t)t * n;
-  // four entries per round: their column loads, then their scale gathers, are in flight together
-  constexpr int R = 4;
-  while (sel) {
-    int32_t c[R];
-    float d[R];
-    bool have[R];
+  for (int j0 = 0; j0 < total; j0 += kWave) {
+    const int j = min(j0 + lane, total - 1);
+    int wj = 0;  // the word that holds selected entry j: the first whose running count exceeds j
 #pragma unroll
-    for (int u = 0; u < R; ++u) {
-      have[u] = sel != 0;
-      const int bit = have[u] ? __ffsll((unsigned long long)sel) - 1 : 0;
-      sel &= sel - 1;  // (stays 0)
-      c[u] = have[u] ? col[bit] : 0;
+    for (int step = kWave >> 1; step >= 1; step >>= 1)
+      if (__shfl(incl, wj + step - 1, kWave) <= j) wj += step;
+    const int r = j - __shfl(excl, wj, kWave);
+    const uint64_t x = (uint64_t)(uint32_t)__shfl((int)sel_lo, wj, kWave) |
+                       ((uint64_t)(uint32_t)__shfl((int)sel_hi, wj, kWave) << 32);
+    const int32_t c = col[wj * 64 + nth_set_bit(x, r)];
+    const float d = dinv_t[c];
+    if (j0 + lane < total) {
+      p.col_out[part][dst0 + j] = c;
+      p.wd[t][dst0 + j] = d;
     }
-#pragma unroll
-    for (int u = 0; u < R; ++u) d[u] = have[u] ? dinv_t[c[u]] : 0.f;
-#pragma unroll
-    for (int u = 0; u < R; ++u)
-      if (have[u]) {
-        p.col_out[part][dst] = c[u];
-        p.wd[t][dst] = d[u];
-        ++dst;
-      }
   }
 }
 
