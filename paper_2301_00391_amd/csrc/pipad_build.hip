@@ -600,7 +600,10 @@ __device__ inline void split_fill_part(const SplitArgs &g, int p, int32_t u, int
   int32_t a, b;
   unit_range(g, p, u, &a, &b);
   const int32_t *col = g.col[p];
-  constexpr int UN = 4;  // chunks in flight per pass
+#ifndef PIPAD_FILL_CHUNKS
+#define PIPAD_FILL_CHUNKS 8
+#endif
+  constexpr int UN = PIPAD_FILL_CHUNKS;  // chunks in flight per pass
   uint32_t cnt[NC];
 #pragma unroll
   for (int x = 0; x < NC; ++x) cnt[x] = 0;
