@@ -74,13 +74,16 @@ SIGNATURES = {
 
 
 def load_library():
-    """Loads libpipad.so (building it first only if it does not exist yet)."""
+    """Loads libpipad.so (building it first only if it does not exist yet).  The environment
+    variable PIPAD_LIBRARY names another build of the library to load instead (measurement builds,
+    see build.py); a missing file is an error, never a fallback."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
+        path = os.environ.get("PIPAD_LIBRARY") or LIB_PATH
+        if path == LIB_PATH and not os.path.exists(LIB_PATH):
             from . import build as _build
             _build.build()
-        lib = ctypes.CDLL(LIB_PATH)
+        lib = ctypes.CDLL(path)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)
             fn.restype = res

@@ -1,4 +1,12 @@
-"""Builds libpipad.so (HIP, gfx950 only) in-tree with hipcc.  Run: python -m paper_2301_00391_amd.build"""
+"""Builds libpipad.so (HIP, gfx950 only) in-tree with hipcc.
+
+    python -m paper_2301_00391_amd.build [-v] [-D NAME[=VALUE] ...] [-o PATH]
+
+-D passes a macro to every source: the measurement builds the profiles are taken with, e.g.
+-D PIPAD_PARTS_MASK=1 (only the class parts of the hub rows run: results incomplete),
+-D PIPAD_AGG_DEPTH=8, -D PIPAD_NO_ROW_ORDER.  -o writes the library somewhere else than in-tree;
+the binding loads the file the environment variable PIPAD_LIBRARY names instead of the in-tree one.
+"""
 from __future__ import annotations
 
 import os
@@ -38,9 +46,9 @@ def check_private_memory(remarks: str, limit: int = 64) -> None:
                                    f"(limit {limit}): kernel arguments copied to scratch?")
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, defines=(), output: str = LIB) -> str:
     """Compiles every HIP source for gfx950 and links the shared library.  Always rebuilds."""
-    flags = [
+    flags = [*[f"-D{d}" for d in defines],
         "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
         # packed fp32 instructions are kept off on this target
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -49,7 +57,7 @@ def build(verbose: bool = False) -> str:
     objs = []
     procs = []
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+        obj = os.path.join(CSRC, src.replace(".hip", f".{os.getpid()}.o"))
         cmd = [hipcc(), *flags, "-Rpass-analysis=kernel-resource-usage", "-c",
                os.path.join(CSRC, src), "-o", obj]
         if verbose:
@@ -62,14 +70,20 @@ def build(verbose: bool = False) -> str:
             sys.stderr.write(err)
             raise RuntimeError("hipcc failed: " + " ".join(cmd))
         check_private_memory(err)
-    link = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    link = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", output, *objs]
     if verbose:
         print(" ".join(link), flush=True)
     subprocess.run(link, check=True)
     for o in objs:
         os.remove(o)
-    return LIB
+    return output
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    import argparse
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("-v", action="store_true", help="print the compiler command lines")
+    ap.add_argument("-D", action="append", default=[], metavar="NAME[=VALUE]")
+    ap.add_argument("-o", default=LIB, metavar="PATH")
+    a = ap.parse_args()
+    print(build(verbose=a.v, defines=a.D, output=a.o))
