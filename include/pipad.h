@@ -182,9 +182,12 @@ int pipad_frame_aggregate_subset(pipad_frame_t *frame, int32_t nsel, const int32
  * the allocator callback is never called.  The call issues no hipMalloc / hipFree and no other
  * allocating routine; the array's address on a device is looked up once, at the first
  * pipad_frame_build_overlap or pipad_frame_aggregate_static on that device.
- *   Returns PIPAD_ERR_SCRATCH, with nothing enqueued, when the frame needs more than the array
- *   holds: (units of rows longer than "mid_max") * (column classes) * k * (F rounded up to the
- *   slice width) floats.
+ *   The partial sums of one snapshot take (units of rows longer than "mid_max") * (column
+ *   classes) * (F rounded up to the slice width) floats.  When the array cannot hold those of all
+ *   k snapshots at once the call goes through the snapshots in groups that fit, one launch after
+ *   the other on `stream` (same bits); when it cannot hold one snapshot's it returns
+ *   PIPAD_ERR_SCRATCH with nothing enqueued.  (The 1M-node benchmark frame at F = 64: 17 MB per
+ *   snapshot, groups of 3.)
  *   All calls on one GPU share the array: calls that overlap in time on that GPU (different
  *   streams, or different frames) race on it and give wrong results; calls ordered on one stream
  *   are safe.  Nothing in the array has to be cleared between calls: every partial sum is written

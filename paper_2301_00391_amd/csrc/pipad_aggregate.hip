@@ -398,10 +398,11 @@ __device__ __forceinline__ int selected_snapshot(const AggArgs &a, int t_seq) {
   return (int)((w >> ((t_seq & 7) * 8)) & 0xffu);
 }
 
-// Where partial sum `slot` (= hub unit * nclass + class) of a slice goes: all partial sums of one
-// slice are contiguous, so a phase writes and the finishing kernel reads dense memory.
-__device__ __forceinline__ float *partial_slot(const AggArgs &a, int slice, int64_t slot, int fl, int vec) {
-  return a.partial + (((int64_t)slice * a.nvp + slot) << a.ls_log2) * vec + fl * vec;
+// Where partial sum `slot` (= hub unit * nclass + class) of the slice_seq-th slice of the call
+// goes: all partial sums of one slice are contiguous, so a phase writes and the finishing kernel
+// reads dense memory, and a call over some of the snapshots needs room for those only.
+__device__ __forceinline__ float *partial_slot(const AggArgs &a, int slice_seq, int64_t slot, int fl, int vec) {
+  return a.partial + (((int64_t)slice_seq * a.nvp + slot) << a.ls_log2) * vec + fl * vec;
 }
 
 template <int VEC, bool FAST, int U, bool UPD>
@@ -618,7 +619,7 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
       reduce_slots<VEC>(a.ls_log2, acc);
       if (split) {
         if (team == 0 && s.fvalid)
-          VT::store(partial_slot(a, slice, v_first + (int64_t)step * a.nclass, fl, VEC), acc, kPartialNt);
+          VT::store(partial_slot(a, slice_seq, v_first + (int64_t)step * a.nclass, fl, VEC), acc, kPartialNt);
       } else if constexpr (UPD) {
         if (team == 0) finish_row_to_sink(a, s, sink, sink.cnt, fl, cur.i, cur.di, cur.xi, acc);
         sink.cnt += 1;
@@ -689,7 +690,7 @@ __global__ __launch_bounds__(kBlock) void k_split_finish(const AggArgs a) {
   typename VT::T acc = VT::zero();
   if (s.fvalid)
     for (int64_t v = v0 + team; v < v1; v += nteams)
-      VT::add(acc, VT::load(partial_slot(a, slice, v, fl, VEC)));
+      VT::add(acc, VT::load(partial_slot(a, slice_seq, v, fl, VEC)));
   reduce_slots<VEC>(a.ls_log2, acc);
   if constexpr (UPD) {
     if (team == 0) {
@@ -1318,9 +1319,25 @@ int aggregate_launch(const pipad_frame *f, int32_t F, const float *const *X, int
 
   // scratch for the partial sums: one slice-wide vector per class part (per hub unit for the
   // coalescent kernel) and slice
-  const size_t need = (coalescent ? (size_t)f->n_items : (size_t)a.nvp) * (size_t)a.nslices * (size_t)sw;
+  const size_t per_snapshot = (size_t)a.nvp * (size_t)a.fchunks * (size_t)sw;  // not coalescent
+  const size_t need = coalescent ? (size_t)f->n_items * (size_t)a.nslices * (size_t)sw
+                                 : per_snapshot * (size_t)a.nsel;
   if (need > *scratch.floats) {
-    if (scratch.fixed) return PIPAD_ERR_SCRATCH;
+    if (scratch.fixed) {
+      // A fixed scratch that is too small for all snapshots at once takes them in groups, one
+      // launch after the other on the stream (a snapshot's result does not depend on what runs
+      // beside it, so the bits are the same); it must hold one snapshot's partial sums.
+      const size_t group = coalescent || per_snapshot == 0 ? 0 : *scratch.floats / per_snapshot;
+      if (group == 0 || a.nsel <= 1) return PIPAD_ERR_SCRATCH;
+      int32_t list[PIPAD_MAX_K];
+      for (int q = 0; q < a.nsel; ++q) list[q] = subset ? subset[q] : q;
+      for (int start = 0; start < a.nsel; start += (int)group) {
+        const int rc = aggregate_launch(f, F, X, ldx, Y, ldy, st, scratch, upd, list + start,
+                                        std::min<int>((int)group, a.nsel - start));
+        if (rc != PIPAD_OK) return rc;
+      }
+      return PIPAD_OK;
+    }
     // growing means allocating: not while the stream is being captured into a graph
     hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(st, &capturing) != hipSuccess) {

@@ -70,6 +70,23 @@ def test_fused_update_on_the_large_frame(pipad, large):
     frame.close()
 
 
+def test_entry_point_without_allocation_on_the_large_frame(pipad, large):
+    """The large frame's partial sums (133 MB for 8 snapshots) do not fit the fixed 64 MiB array at
+    once: pipad_frame_aggregate_static takes the snapshots in groups of three and must give the
+    bits of pipad_frame_aggregate."""
+    cfg, s = large
+    n, k, F = cfg.n, cfg.k, cfg.feat
+    dev = "cuda:0"
+    frame = pipad.frame_build_overlap(to_gpu_snapshots(torch, s, range(k)))
+    xs = [torch.from_numpy(synth.features(cfg.seed, t, n, F)).to(dev) for t in range(k)]
+    y_alloc = [y.clone() for y in pipad.frame_aggregate(frame, xs)]
+    y_static = pipad.frame_aggregate(frame, xs, static_scratch=True)
+    torch.cuda.synchronize()
+    for t in range(k):
+        assert torch.equal(y_alloc[t], y_static[t]), f"snapshot {t}"
+    frame.close()
+
+
 @pytest.mark.parametrize("F", [2, 16])
 def test_coalescent_kernel_on_the_large_frame(pipad, large, F):
     """Default options: the concatenated [N, k, F] operand of 64 / 512 MB takes the coalescent

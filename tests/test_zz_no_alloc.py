@@ -99,18 +99,50 @@ def test_static_scratch_entry_point_matches_the_allocating_one(pipad):
             pipad.set_option(key, val)
 
 
+def test_static_scratch_entry_point_takes_the_snapshots_in_groups(pipad):
+    """A frame whose partial sums fit the fixed array for one snapshot (about 5 k units x 8 classes
+    x 128 floats = 20 MB) but not for all 8: the call goes through the snapshots in groups of
+    three, one launch after the other, and still gives the bits of the allocating entry point."""
+    from paper_2301_00391_amd import binding
+    lib = pipad.load_library()
+    saved = {key: pipad.get_option(key) for key in ("short_max", "mid_max", "hub_threshold", "hub_segment")}
+    try:
+        pipad.set_option("short_max", 0)
+        pipad.set_option("mid_max", 0)
+        pipad.set_option("hub_threshold", 1)
+        pipad.set_option("hub_segment", 1)
+        rng = np.random.default_rng(6)
+        n, k, F = 1000, 8, 128
+        lists = churned(rng, n, k, 0.005, 0.9)
+        frame, _snaps = build_frame_abi(lib, binding, lists, n)
+        Xh = [synth.features(12, t, n, F) for t in range(k)]
+        X = [torch.from_numpy(x).cuda() for x in Xh]
+        y_alloc, y_static = both_entry_points(lib, frame, X, n, k, F)
+        for t in range(k):
+            assert torch.equal(y_alloc[t], y_static[t]), f"snapshot {t} differs"
+        for t in (0, k - 1):
+            rows, cols = csr_to_coo(n, *lists[t])
+            _, yd, bound, _ = oracle.aggregate(n, rows, cols, Xh[t], threads=4)
+            check_y(y_static[t].cpu().numpy(), yd, bound, f"static in groups, snapshot {t}")
+        lib.pipad_frame_destroy(frame)
+    finally:
+        for key, val in saved.items():
+            pipad.set_option(key, val)
+
+
 def test_static_scratch_entry_point_rejects_what_does_not_fit(pipad):
     from paper_2301_00391_amd import binding
     lib = pipad.load_library()
     saved = {key: pipad.get_option(key) for key in ("short_max", "mid_max", "hub_threshold", "hub_segment")}
     try:
-        # every entry a unit of its own: about 10 k units x 8 classes x k*F = 1024 floats > 64 MiB
+        # every entry a unit of its own: about 20 k units x 8 classes x F = 128 floats for ONE
+        # snapshot > 64 MiB
         pipad.set_option("short_max", 0)
         pipad.set_option("mid_max", 0)
         pipad.set_option("hub_threshold", 1)
         pipad.set_option("hub_segment", 1)
         rng = np.random.default_rng(5)
-        n, k, F = 1000, 8, 128
+        n, k, F = 2000, 8, 128
         lists = churned(rng, n, k, 0.005, 1.0)
         frame, _snaps = build_frame_abi(lib, binding, lists, n)
         X = [torch.zeros((n, F), device="cuda:0") for _ in range(k)]
