@@ -2,7 +2,7 @@
 //
 // Section 4.1 ("Overlap-aware data transfer") regroups the topology of a snapshot group as one
 // overlap part plus one exclusive part per snapshot; Section 4.3 makes this the job of a data
-// preparation module that runs once.  Here it runs on the GPU, edge-parallel, in four steps:
+// preparation module that runs once.  Here it runs on the GPU, edge-parallel, in five steps:
 //
 //   mark     one lane per stored entry of snapshot 0: find its row, then binary-search its column
 //            in the same row of every other snapshot.  An entry found everywhere is a common
@@ -15,12 +15,14 @@
 //   scatter  every selected entry is written to prefix[word] + (set bits below it in its word),
 //            which keeps the ascending column order of the input (stable compaction); the
 //            per-entry column scales are written alongside.
+//   lists    rows binned by length into the work lists of the aggregation (short, mid, hub; very
+//            long rows cut into units), and the entries of the hub rows stored a second time,
+//            grouped by column class, with their scales.
 //
 // All integer work; the outputs are unique, so they are bit-exact regardless of scheduling (the
-// marks are plain byte stores with one writer each; there are no atomics).
+// marks are plain byte stores with one writer each; the only atomics are integer additions that
+// sum up sizes).
 #include <algorithm>
-#include <cstring>
-
 #include <cstring>
 
 #include "pipad_internal.h"
