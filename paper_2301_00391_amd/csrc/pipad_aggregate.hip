@@ -489,7 +489,11 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
   const int64_t n_items = a.n_items, n_mid = a.n_long, n_short = a.n_short;
   const int b_wide = a.batch_wide, b_mid = a.batch_mid, b_short = a.batch_short;
   const bool split = w < split_blocks;                  // class parts of hub units
+#ifdef PIPAD_SPLIT_TEAM  // measurement builds: class parts walked by lane teams like short rows
+  const bool wide = !split && w < split_blocks + a.blocks_mid;
+#else
   const bool wide = w < split_blocks + a.blocks_mid;    // ... or whole mid rows: a wave per list
+#endif
   int cls = 0;  // column class of this wave's class parts
   if (split) {
     const int sub = (int)(w / wide_blocks);  // the sub classes come one after the other in time
@@ -576,6 +580,7 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
   const int nslots = wide ? nteams : 1;
 
   struct Item {
+    int src;  // place of the element in the wave's batch
     int32_t i, cs, clen, ds, dlen;
     float di;
     bool have;
@@ -587,6 +592,7 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
     const int li = step * per_step + (wide ? 0 : team);
     it.have = li < rows_here;
     const int src = __shfl(order, it.have ? li : 0, kWave);
+    it.src = src;
     it.i = __shfl(r, src, kWave);
     it.cs = __shfl(mc0, src, kWave);
     it.clen = __shfl(mc1, src, kWave) - it.cs;
@@ -631,7 +637,10 @@ __device__ __forceinline__ void aggregate_body(const AggArgs &a) {
         walk<VEC, US, FAST>(colc, wcs, cur.cs, cur.clen, cur.fc, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
         walk<VEC, US, FAST>(cold, wds, cur.ds, cur.dlen, cur.fd, team_base, team_lanes, q, slot, nslots, s, a.ldx, cur.i, ntl, lds, acc);
       }
-      if constexpr (UPD) {
+      if (split) {  // (PIPAD_SPLIT_TEAM builds only)
+        if (cur.have && s.fvalid)
+          VT::store(partial_slot(a, slice_seq, v_first + (int64_t)cur.src * a.nclass, fl, VEC), acc, kPartialNt);
+      } else if constexpr (UPD) {
         if (cur.have) finish_row_to_sink(a, s, sink, sink.cnt + team, fl, cur.i, cur.di, cur.xi, acc);
         sink.cnt += rows_now;  // teams 0 .. rows_now - 1 had a row
       } else {
