@@ -27,6 +27,10 @@
 
 #include "pipad_internal.h"
 
+#ifndef PIPAD_DENSE_FACTOR
+#define PIPAD_DENSE_FACTOR 3  // exclusive entries from all / this on take the lane-per-entry scatter
+#endif
+
 namespace pipad {
 namespace {
 
@@ -1195,7 +1199,7 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
       excl += f->nnz_d[t];
       max_nnz = std::max(max_nnz, s.nnz[t]);
     }
-    if (excl * 8 > all) {  // not sparse enough for the per-word walk: a lane per entry
+    if (excl * PIPAD_DENSE_FACTOR > all) {  // mostly selected: a lane per entry
       hipLaunchKernelGGL(k_scatter_delta_dense, grid1(max_nnz, kBlock, k), dim3(kBlock), 0, st, s, p,
                          pre, f->dinv, n);
     } else if (max_nw > 0) {

@@ -151,6 +151,38 @@ def test_row_classes_short_mid_hub(pipad, short_max, mid_max, threshold, segment
     run_case(pipad, n, lists, 3, seed=10, layout="wide")
 
 
+@pytest.mark.parametrize("keep", [0.95, 0.3])
+def test_column_arrays_that_are_only_4_byte_aligned(pipad, keep):
+    """The ABI asks for int32 alignment only: column arrays that start in the middle of a 16-byte
+    piece are valid input (little overlap: the lane-per-entry scatter of the exclusive parts; much
+    overlap: the expand)."""
+    rng = np.random.default_rng(int(keep * 100))
+    n, k, F = 800, 4, 32
+    lists = churned(rng, n, k, 0.03, keep)
+    dev = "cuda:0"
+    snaps, hold = [], []
+    for rp, c in lists:
+        store = torch.zeros(c.size + 3, dtype=torch.int32, device=dev)
+        for shift in (1, 2, 3):
+            if (store.data_ptr() + 4 * shift) % 16 != 0:
+                break
+        view = store[shift:shift + c.size]
+        view.copy_(torch.from_numpy(c).to(dev))
+        assert view.data_ptr() % 16 != 0 and view.is_contiguous()
+        hold.append(store)
+        snaps.append((torch.from_numpy(rp).to(dev), view))
+    frame = pipad.frame_build_overlap(snaps)
+    coo = [csr_to_coo(n, rp, c) for rp, c in lists]
+    check_overlap(frame, oracle.overlap(n, coo))
+    X = [synth.features(5, t, n, F) for t in range(k)]
+    ys = pipad.frame_aggregate(frame, [torch.from_numpy(x).to(dev) for x in X])
+    torch.cuda.synchronize()
+    for t in range(k):
+        _, yd, bound, _ = oracle.aggregate(n, coo[t][0], coo[t][1], X[t], threads=4)
+        check_y(ys[t].cpu().numpy(), yd, bound, f"snapshot {t}")
+    frame.close()
+
+
 def test_a_frame_keeps_the_options_it_was_built_with(pipad):
     """Options are copied into the frame by the build: changing them afterwards must not change a
     bit of what the frame computes, while a frame built afterwards takes the new values (here: all
