@@ -276,7 +276,8 @@ def main() -> int:
                          "three times (1 GiB each): a profiler's traffic counters are scaled by what "
                          "they read for it")
     ap.add_argument("--sweep", default=None,
-                    choices=["overlap", "features", "sliding", "workloads", "smallf", "rows", "labels", "oracle"],
+                    choices=["overlap", "features", "sliding", "workloads", "smallf", "rows", "labels", "oracle",
+                             "partitions"],
                     help="print one of the sensitivity tables (bench_sweeps.py) instead of the bench line")
     ap.add_argument("--ceilings", action="store_true",
                     help="only measure the streaming and gather ceilings of this GPU (full sweep) "

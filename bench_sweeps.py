@@ -13,6 +13,7 @@ on the synthetic generator instead of the paper's datasets.
   python bench.py --sweep rows       # row-length classes: thresholds of the three kinds of work items
   python bench.py --sweep labels     # the large frame with its nodes relabelled (locality sensitivity)
   python bench.py --sweep oracle     # the CPU oracle on one thread and on all threads
+  python bench.py --sweep partitions # a group of 8 snapshots as 8 / S_per frames of S_per: the tuner's table
 
 Every cell times ``pipad_frame_aggregate`` of one frame of k snapshots and, as the baseline, the
 same k snapshots aggregated one at a time (k frames of a single snapshot each, whose overlap part
@@ -340,6 +341,48 @@ def label_sweep(dev):
         print(f"| {label} | {cells[0]:.3f} | {cells[1]:.3f} |", flush=True)
 
 
+def partition_sweep(dev):
+    """The decision the paper's tuner takes (Section 4.4): how many snapshots S_per of a group
+    share one overlap part.  A group of 8 snapshots is processed as 8 / S_per frames of S_per
+    snapshots each; one cell = aggregation ms for the 8 snapshots [+ extraction ms for them],
+    the best S_per of the row marked."""
+    n, edges = 200_000, 1_600_000
+    print(f"Chung-Lu gamma 2.1, N = {n}, {edges} undirected edges per snapshot, 8 snapshots; cell = "
+          "aggregation ms + extraction ms for all 8 snapshots (concatenated operand for F < 32)\n")
+    print("| churn per step | F | " + " | ".join(f"S_per = {sp}" for sp in (1, 2, 4, 8)) + " | best by aggregation | best with extraction |")
+    print("|---|---|---|---|---|---|---|---|")
+    for churn in (0.01, 0.10, 0.40):
+        snaps = synth.graphs(n, edges, 8, churn, "chung-lu", (2.1, 16.0), seed=2)
+        gs = [(torch.from_numpy(snaps.rowptr[t]).to(dev), torch.from_numpy(snaps.col[t]).to(dev))
+              for t in range(8)]
+        for feat in (2, 16, 64):
+            cells, agg, tot = [], [], []
+            for sp in (1, 2, 4, 8):
+                groups = [gs[i:i + sp] for i in range(0, 8, sp)]
+                t_build = min(_time(lambda: [pipad.frame_build_overlap(g).close() for g in groups], reps=1)
+                              for _ in range(3))
+                frames = [pipad.frame_build_overlap(g) for g in groups]
+                if feat < 32:
+                    xs = [torch.rand((n, sp, feat), device=dev) * 2 - 1 for _ in groups]
+                else:
+                    xs = [[torch.rand((n, feat), device=dev) * 2 - 1 for _ in range(sp)] for _ in groups]
+                ys = [torch.empty_like(x) if feat < 32 else [torch.empty_like(v) for v in x] for x in xs]
+
+                def run():
+                    for f, x, y in zip(frames, xs, ys):
+                        pipad.frame_aggregate(f, x, y)
+                t_agg = _time(run)
+                for f in frames:
+                    f.close()
+                cells.append(f"{t_agg:.3f} + {t_build:.3f}")
+                agg.append(t_agg)
+                tot.append(t_agg + t_build)
+                del xs, ys
+            sps = (1, 2, 4, 8)
+            print(f"| {churn:.0%} | {feat} | " + " | ".join(cells) +
+                  f" | {sps[int(np.argmin(agg))]} | {sps[int(np.argmin(tot))]} |", flush=True)
+
+
 def oracle_sweep(dev):
     """The CPU oracle (plain per-snapshot aggregation in double, never tuned) on this host: one
     thread and all hardware threads, one snapshot of every benchmark frame."""
@@ -385,6 +428,8 @@ def main(argv):
         label_sweep(dev)
     elif which == "oracle":
         oracle_sweep(dev)
+    elif which == "partitions":
+        partition_sweep(dev)
     else:
         print(__doc__, file=sys.stderr)
         return 2
