@@ -715,9 +715,15 @@ __global__ __launch_bounds__(kBlock) void k_split_fill(SplitArgs g) {
 // Common part: one lane per stored entry of snapshot 0 (most of them are selected); the entry's k
 // column scales come from the node-major copy of D^-1/2 (one line per node).
 // KV > 0: k == 4 * KV, a node's k scales are read as KV 16-byte pieces; KV == 0: any k, one by one.
+// The scales of a hub row's entries are never read from here (the aggregation takes them from the
+// class-grouped copy, k_split_scales): a wave whose 64 entries all lie in one hub row - most waves
+// of such a row - skips them.  wave_row / hubidx: as written by k_wave_rows and the scan of
+// k_classify's hub flags.
 template <int KV>
 __global__ __launch_bounds__(kBlock) void k_scatter_common(Snaps s, Parts p, const uint32_t *pre,
-                                                            const float *dinv_nk, int32_t k) {
+                                                            const float *dinv_nk, int32_t k,
+                                                            const int32_t *wave_row,
+                                                            const uint32_t *hubidx, int32_t n) {
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (e >= s.nnz[0]) return;
   const uint32_t w = (uint32_t)(e >> 6), bit = (uint32_t)(e & 63);
@@ -726,6 +732,11 @@ __global__ __launch_bounds__(kBlock) void k_scatter_common(Snaps s, Parts p, con
   const uint32_t dst = pre[w] - pre[0] + (uint32_t)__popcll(sel & ((1ull << bit) - 1ull));
   const int32_t c = s.col[0][e];
   p.col_out[0][dst] = c;
+  const int32_t r0 = wave_row[w], r1 = wave_row[w + 1];  // rows of this and of the next wave's first entry
+  if (r0 == r1) {
+    const int32_t r = min(max(r0, 0), n - 1);
+    if (hubidx[r + 1] != hubidx[r]) return;
+  }
   if (KV > 0) {
     const float4 *row = reinterpret_cast<const float4 *>(dinv_nk) + (int64_t)c * KV;
     float4 v[KV > 0 ? KV : 1];
@@ -1189,7 +1200,8 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
   if (s.nnz[0] > 0) {
     auto scatter = k == 4 ? k_scatter_common<1> : k == 8 ? k_scatter_common<2>
                  : k == 16 ? k_scatter_common<4> : k_scatter_common<0>;
-    hipLaunchKernelGGL(scatter, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, pre, f->dinv_nk, k);
+    hipLaunchKernelGGL(scatter, grid1(s.nnz[0], kBlock), dim3(kBlock), 0, st, s, p, pre, f->dinv_nk, k,
+                       wave_row, hubidx, n);
   }
   {
     int64_t all = 0, excl = 0;
