@@ -36,7 +36,7 @@ struct Options {
   int64_t sub_classes = 1;      // column classes per XCD for hub rows (1, 2 or 4), taken one after the other
   int64_t agg_order = 2;        // workgroup order: 0 slices side by side, 1 one slice after the other, 2 by operand size
   // kernel choices of the aggregation
-  int64_t agg_nt = 0;           // bit 0: non-temporal Y stores, bit 1: non-temporal index streams
+  int64_t agg_nt = 1;           // bit 0: non-temporal Y stores, bit 1: non-temporal index streams
   int64_t agg_coalescent = 1;   // small-F coalescent kernel: 0 never, 1 automatic, 2 whenever possible
   int64_t slice_cols = 0;       // columns per slice (0: automatic, else at most 64)
   int64_t agg_generic = 0;      // 1: force the generic (bounds-checked, 64-bit address) kernel

@@ -34,9 +34,10 @@ def test_host_only_calls():
     assert lib.pipad_strerror(-2).startswith(b"snapshot")
     assert lib.pipad_strerror(12345) == b"unknown status"
     assert lib.pipad_last_hip_error() == b""
+    before = pipad.get_option("agg_nt")
     pipad.set_option("agg_nt", 2)
     assert pipad.get_option("agg_nt") == 2
-    pipad.set_option("agg_nt", 0)
+    pipad.set_option("agg_nt", before)
     assert lib.pipad_set_option(b"no_such_key", 1) == -1
     # argument checks that need no device
     out = ctypes.c_void_p()

@@ -13,7 +13,7 @@ from _util import check_overlap, check_y, csr_to_coo, to_gpu_snapshots
 pytestmark = pytest.mark.gpu
 
 DEFAULT_OPTIONS = {"short_max": 64, "mid_max": 512, "hub_threshold": 2048, "hub_segment": 2048,
-                   "sub_classes": 1, "agg_order": 2, "agg_nt": 0, "agg_generic": 0, "agg_coalescent": 1, "slice_cols": 0}
+                   "sub_classes": 1, "agg_order": 2, "agg_nt": 1, "agg_generic": 0, "agg_coalescent": 1, "slice_cols": 0}
 
 torch = pytest.importorskip("torch")
 
