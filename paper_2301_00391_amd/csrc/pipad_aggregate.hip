@@ -283,10 +283,14 @@ __device__ __forceinline__ void walk(const int32_t *__restrict__ col, const floa
       }
 #pragma unroll
       for (int u = 0; u < UNR; ++u) {
+#ifdef PIPAD_NO_GATHER  // measurement builds: everything but the row gathers (wrong results)
+        x[u] = VT::zero();
+#else
         if (FAST)
           x[u] = VT::load(reinterpret_cast<const float *>(xbytes + (en[u].off + lane_bytes)));
         else
           x[u] = VT::load(xcol + (int64_t)en[u].off * ldx);
+#endif
       }
 #pragma unroll
       for (int u = 0; u < UNR; ++u) VT::fma(acc, en[u].w, x[u]);
