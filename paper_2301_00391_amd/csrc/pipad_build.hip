@@ -1151,8 +1151,12 @@ int build_overlap(int32_t n, int32_t k, const pipad_csr_t *snaps, uint32_t flags
     copied = nullptr;
   }
   if (!copied) host_totals = stack_totals;
-  PIPAD_TRY(hipMemcpyAsync(host_totals, totals, sizeof(uint32_t) * (size_t)(2 * k + 6),
-                           hipMemcpyDeviceToHost, st));
+  {
+    const hipError_t ce = hipMemcpyAsync(host_totals, totals, sizeof(uint32_t) * (size_t)(2 * k + 6),
+                                         hipMemcpyDeviceToHost, st);
+    if (ce != hipSuccess && copied) (void)hipEventDestroy(copied);
+    PIPAD_TRY(ce);
+  }
   if (copied) {
     hipError_t e = hipEventRecord(copied, st);
     if (e == hipSuccess && n > 0)
