@@ -130,6 +130,47 @@ def test_static_scratch_entry_point_takes_the_snapshots_in_groups(pipad):
             pipad.set_option(key, val)
 
 
+def test_static_scratch_entry_point_recorded_into_a_hip_graph_without_an_eager_call(pipad):
+    """What the entry point is for: a fresh frame (its own scratch buffer was never sized) goes
+    straight into a stream capture; every replay, with eager work and synchronisations in between,
+    must give the bits of the eager allocating call."""
+    saved = {key: pipad.get_option(key) for key in ("short_max", "mid_max", "hub_threshold", "hub_segment")}
+    try:
+        pipad.set_option("short_max", 2)
+        pipad.set_option("mid_max", 5)
+        pipad.set_option("hub_threshold", 6)
+        pipad.set_option("hub_segment", 4)
+        rng = np.random.default_rng(123)
+        n, k, F = 700, 3, 64
+        lists = churned(rng, n, k, 0.03, 0.8)
+        dev = "cuda:0"
+        snaps = [(torch.from_numpy(rp).to(dev), torch.from_numpy(c).to(dev)) for rp, c in lists]
+        frame = pipad.frame_build_overlap(snaps)
+        other = pipad.frame_build_overlap(snaps)  # for the eager reference
+        X = [torch.from_numpy(synth.features(7, t, n, F)).to(dev) for t in range(k)]
+        Y = [torch.empty_like(x) for x in X]
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            pipad.frame_aggregate(frame, X, Y, static_scratch=True)
+        for replay in range(3):
+            for t in range(k):
+                X[t].copy_(torch.from_numpy(synth.features(200 + replay, t, n, F)))
+            want = [y.clone() for y in pipad.frame_aggregate(other, X)]
+            torch.cuda.synchronize()
+            for y in Y:
+                y.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            for t in range(k):
+                assert torch.equal(Y[t], want[t]), f"replay {replay}, snapshot {t}"
+        frame.close()
+        other.close()
+    finally:
+        for key, val in saved.items():
+            pipad.set_option(key, val)
+
+
 def test_static_scratch_entry_point_rejects_what_does_not_fit(pipad):
     from paper_2301_00391_amd import binding
     lib = pipad.load_library()
