@@ -4,8 +4,9 @@
 // of an intersection is the intersection of the transposes - and all 1 + k parts go through the
 // same launches.  Transposing a CSR pattern is a stable sort of its entries by column: rows arrive
 // in ascending order, so they leave in ascending order within every column, which makes the result
-// canonical CSR again.  The sort is a least-significant-digit radix sort on 8-bit digits of the
-// column index, written for 64-lane waves:
+// canonical CSR again.  The sort is a least-significant-digit radix sort on 6-bit digits of the
+// column index (measured against 7 and 8 bits: fewer ballots per entry and longer contiguous
+// runs per digit outweigh the extra pass), written for 64-lane waves:
 //
 //   tiles      a part is cut into tiles of 2048 consecutive entries, one wave per tile
 //   histogram  per tile and digit value; lanes of a wave that hold the same digit find each other
@@ -26,7 +27,7 @@ namespace pipad {
 namespace {
 
 #ifndef PIPAD_SORT_DIGIT
-#define PIPAD_SORT_DIGIT 8
+#define PIPAD_SORT_DIGIT 6
 #endif
 constexpr int kDigitBits = PIPAD_SORT_DIGIT;
 constexpr int kDigits = 1 << kDigitBits;
@@ -239,17 +240,35 @@ struct ScaleArgs {
   float *wd[PIPAD_MAX_K];
 };
 
+// KV > 0: k == 4 * KV, a node's k scales are read as KV 16-byte pieces and the k destination
+// arrays are fixed at compile time; KV == 0: any k, one by one.
+template <int KV>
 __global__ __launch_bounds__(kBlock) void k_part_scales(ScaleArgs g) {
   const int64_t e64 = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (e64 >= g.part_off[g.nparts]) return;
   const uint32_t e = (uint32_t)e64;
-  const int p = part_of(g.part_off, g.nparts, e);
-  const uint32_t local = e - g.part_off[p];
-  const int32_t c = g.col[p][local];
-  if (p == 0) {
-    const float *row = g.dinv_nk + (int64_t)c * g.k;
-    for (int t = 0; t < g.k; ++t) g.wc[t][local] = row[t];
+  if (e < g.part_off[1]) {  // overlap part
+    const int32_t c = g.col[0][e];
+    if (KV > 0) {
+      const float4 *row = reinterpret_cast<const float4 *>(g.dinv_nk) + (int64_t)c * KV;
+      float4 v[KV > 0 ? KV : 1];
+#pragma unroll
+      for (int q = 0; q < KV; ++q) v[q] = row[q];
+#pragma unroll
+      for (int q = 0; q < KV; ++q) {
+        g.wc[4 * q + 0][e] = v[q].x;
+        g.wc[4 * q + 1][e] = v[q].y;
+        g.wc[4 * q + 2][e] = v[q].z;
+        g.wc[4 * q + 3][e] = v[q].w;
+      }
+    } else {
+      const float *row = g.dinv_nk + (int64_t)c * g.k;
+      for (int t = 0; t < g.k; ++t) g.wc[t][e] = row[t];
+    }
   } else {
+    const int p = part_of(g.part_off, g.nparts, e);
+    const uint32_t local = e - g.part_off[p];
+    const int32_t c = g.col[p][local];
     g.wd[p - 1][local] = g.dinv[(int64_t)(p - 1) * g.n + c];
   }
 }
@@ -430,7 +449,9 @@ int transpose_frame(const pipad_frame *f, pipad_alloc_fn alloc, void *alloc_ctx,
       c.wc[t] = g->wc[t];
       c.wd[t] = g->wd[t];
     }
-    hipLaunchKernelGGL(k_part_scales, grid1(total, kBlock), dim3(kBlock), 0, st, c);
+    auto scales = k == 4 ? k_part_scales<1> : k == 8 ? k_part_scales<2> : k == 16 ? k_part_scales<4>
+                                                                                   : k_part_scales<0>;
+    hipLaunchKernelGGL(scales, grid1(total, kBlock), dim3(kBlock), 0, st, c);
   }
   PIPAD_TRY_T(hipGetLastError());
 
