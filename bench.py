@@ -101,9 +101,12 @@ def write_traffic_profile(workload: str, dirs, bench_line: dict) -> None:
 
     kt, pf, pw, pl = dirs
     fo = bench_line["config"].get("fused_update_cols", 0)
-    args = f"--workload {workload} --steps {bench_line['steps']} --warmup {bench_line['warmup']} --no-cpu"
+    args = f"--workload {workload} --steps {bench_line['steps']} --warmup {bench_line['warmup']}"
     if fo:
         args += f" --update {fo}"
+    counter_args = args + " --no-cpu --calibrate-counters"  # the counter runs skip the CPU leg
+    if "cpu_baseline" not in bench_line:
+        args += " --no-cpu"
     tag = f"{workload}_update" if fo else workload
     agg_kernels = ("k_aggregate_update", "k_split_finish") if fo else ("k_aggregate", "k_split_finish")
     head = (f"# bench.py, workload {workload} (N={bench_line['config']['n']}, k={bench_line['config']['k']}, "
@@ -154,7 +157,7 @@ def write_traffic_profile(workload: str, dirs, bench_line: dict) -> None:
          f"# cache) of one {'pipad_frame_aggregate_update' if fo else 'pipad_frame_aggregate'} call = {agg_kernels[0]} + "
          "k_split_finish; rocprofv3 counters, KiB per dispatch.",
          f"# commands (from the repository root, one run each): export TMPDIR=/tmp && rocprofv3 --pmc FETCH_SIZE -d <out> -o bench "
-         f"--output-format csv -- python3 bench.py {args} --calibrate-counters",
+         f"--output-format csv -- python3 bench.py {counter_args}",
          "#                              ... --pmc WRITE_SIZE ...  |  ... --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum ...",
          "# summary written by: python3 bench.py --profile-summary <kernel-trace dir> <FETCH dir> <WRITE dir> <L2 dir> "
          f"--workload {workload}  (bench line of the kernel-trace run on stdin)",
